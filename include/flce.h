@@ -1,0 +1,122 @@
+/*
+ * flce - fused lm_head projection + cross-entropy loss for AMD MI355X (gfx950).
+ *
+ * C ABI.  Computes, from hidden states H[N,d], vocabulary weights W[V,d] and
+ * integer targets y[N], the cross-entropy loss of the logits Z = H.W^T and its
+ * gradients dH, dW, without ever storing the N x V logits (the paper's
+ * Section 3.2: the direct loss of Eq. 3, the streaming forward of Alg. 1, the
+ * recompute backward of Alg. 2 / Eq. 4 / Eq. 5, and the window strategy with
+ * its merging epilogue of Section 3.2.1).
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller, row-major and
+ *     contiguous: H[N][d], W[V][d], dH[N][d], dW[V][d]; 16-byte aligned.
+ *   - Element type of H, W, dH, dW is `dt`: bf16 (2 bytes) or fp32.  Logits,
+ *     softmax statistics and all accumulations are fp32; loss and lse are fp32.
+ *   - targets are int64, 0-based, in [0, V).  A row whose target equals
+ *     `ignore_index` (any int64 value; compared first) does not count: its loss
+ *     is 0, its dH row is all +0, it adds nothing to dW and it is left out of
+ *     the mean's denominator.  A counted target outside [0, V) is an input
+ *     error: the row is treated as ignored and FLCE_ERR_TARGET_RANGE is latched
+ *     in the workspace (read it with flce_last_device_status).
+ *   - The library never allocates device memory.  Scratch comes from the
+ *     caller's `workspace` (size from flce_workspace_bytes; 256-byte aligned);
+ *     it holds no N x V term.  The workspace contents are undefined on entry
+ *     and between calls; forward and backward may use the same buffer.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t, NULL = the default
+ *     stream) and the calls return without synchronising.  Outputs are fully
+ *     overwritten.  Results are bit-identical from run to run for the same
+ *     inputs, shapes and tuning environment: no floating-point atomics, every
+ *     sum has a fixed order.
+ *   - Host-detectable errors (null pointer, non-positive size, d not a multiple
+ *     of 8, workspace too small, unknown enum) return a status and launch
+ *     nothing.  A failing HIP runtime call returns FLCE_ERR_HIP.  Nothing is
+ *     printed, nothing throws.
+ *   - Re-entrant: all state lives in the caller's workspace.  Concurrent calls
+ *     must use distinct workspaces.
+ *   - n_valid == 0 gives loss 0 and zero gradients (both reductions).
+ */
+#ifndef FLCE_H_
+#define FLCE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FLCE_OK = 0,
+  FLCE_ERR_BAD_ARG = 1,      /* null pointer, unknown enum value */
+  FLCE_ERR_BAD_SHAPE = 2,    /* N, d or V <= 0, d % 8 != 0, sizes beyond 2^31-1 rows */
+  FLCE_ERR_WORKSPACE = 3,    /* workspace null, misaligned or smaller than required */
+  FLCE_ERR_TARGET_RANGE = 4, /* a counted target was outside [0, V) (device-detected) */
+  FLCE_ERR_UNSUPPORTED = 5,  /* reserved (e.g. reduction "none") */
+  FLCE_ERR_HIP = 6           /* a HIP runtime call failed */
+} flce_status;
+
+typedef enum { FLCE_DTYPE_BF16 = 0, FLCE_DTYPE_F32 = 1 } flce_dtype;
+
+/* mean: divide by the number of counted rows (Eq. 2 / Alg. 1's last step, with
+ * B*T replaced by n_valid); sum: no division. */
+typedef enum { FLCE_REDUCE_MEAN = 0, FLCE_REDUCE_SUM = 1 } flce_reduction;
+
+/* Library version, "major.minor.patch". Host call. */
+const char* flce_version(void);
+
+/* Static, human-readable name of a status code. Host call. */
+const char* flce_status_string(flce_status s);
+
+/*
+ * Bytes of device workspace needed by flce_forward (for_backward == 0) or
+ * flce_backward (for_backward != 0) at this shape.  Returns 0 for an invalid
+ * shape or dtype.  Grows like c1*(N+V)*d + c2*N + c3 with fixed-size staging
+ * buffers: there is no N*V term.  Host call, touches no device.
+ */
+size_t flce_workspace_bytes(int64_t N, int64_t d, int64_t V, flce_dtype dt, int for_backward);
+
+/*
+ * Forward (Alg. 1 over tiles, Section 3.2.1 windows + merging epilogue).
+ *   H, W, targets : device, read-only.
+ *   loss_out      : device, 1 float.  mean or sum of (lse_i - z_{i,y_i}) over counted rows.
+ *   lse_out       : device, N floats. lse_i = log sum_v exp(Z_iv) for EVERY row,
+ *                   ignored ones included (this is m + ln a of Alg. 1; it is what
+ *                   flce_backward takes back in place of the pair (m, a)).
+ * Returns FLCE_OK once the work is enqueued.
+ */
+flce_status flce_forward(const void* H, const void* W, const int64_t* targets,
+                         int64_t N, int64_t d, int64_t V, int64_t ignore_index,
+                         flce_reduction reduction, flce_dtype dt,
+                         float* loss_out, float* lse_out,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward (Alg. 2: logits recomputed tile by tile, G = p - onehot formed from
+ * the saved lse, then Eq. 4 dH = G.W and Eq. 5 dW = G^T.H as MFMA contractions).
+ *   lse        : device, N floats, as written by flce_forward for the same inputs.
+ *   grad_loss  : upstream gradient of the scalar loss (host value).  Every
+ *                counted row gets Gamma = grad_loss / n_valid (mean) or grad_loss (sum).
+ *   dH_out     : device, N*d elements of type dt.
+ *   dW_out     : device, V*d elements of type dt.
+ * G is rounded to `dt` before the two contractions (unscaled, |G| <= 1); Gamma
+ * is applied in fp32 when the fp32 sums are written out.
+ */
+flce_status flce_backward(const void* H, const void* W, const int64_t* targets, const float* lse,
+                          int64_t N, int64_t d, int64_t V, int64_t ignore_index,
+                          flce_reduction reduction, flce_dtype dt, float grad_loss,
+                          void* dH_out, void* dW_out,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Synchronises `hip_stream`, then reports what the last flce_forward or
+ * flce_backward that used `workspace` latched on the device: FLCE_OK or
+ * FLCE_ERR_TARGET_RANGE (FLCE_ERR_HIP if the synchronisation or copy fails).
+ * If n_valid_out is not NULL it receives the number of counted rows (host).
+ */
+flce_status flce_last_device_status(const void* workspace, void* hip_stream, int64_t* n_valid_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLCE_H_ */

@@ -1,0 +1,99 @@
+"""ctypes binding of libflce.so: the same names and arguments as include/flce.h.
+
+Argument marshalling only.  Pointers may be given as integers (device
+addresses) or as objects with a ``data_ptr()`` method (torch tensors); streams
+as integers or objects with a ``cuda_stream`` attribute.  A missing library
+raises: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libflce.so")
+
+FLCE_OK, FLCE_ERR_BAD_ARG, FLCE_ERR_BAD_SHAPE, FLCE_ERR_WORKSPACE = 0, 1, 2, 3
+FLCE_ERR_TARGET_RANGE, FLCE_ERR_UNSUPPORTED, FLCE_ERR_HIP = 4, 5, 6
+FLCE_DTYPE_BF16, FLCE_DTYPE_F32 = 0, 1
+FLCE_REDUCE_MEAN, FLCE_REDUCE_SUM = 0, 1
+
+EXPORTS = ("flce_version", "flce_status_string", "flce_workspace_bytes", "flce_forward", "flce_backward",
+           "flce_last_device_status")
+
+_lib = None
+
+
+def lib():
+    """The loaded library (opened on first use)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_17599_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        c = ctypes
+        L.flce_version.restype = c.c_char_p
+        L.flce_version.argtypes = []
+        L.flce_status_string.restype = c.c_char_p
+        L.flce_status_string.argtypes = [c.c_int]
+        L.flce_workspace_bytes.restype = c.c_size_t
+        L.flce_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_int]
+        L.flce_forward.restype = c.c_int
+        L.flce_forward.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_int64,
+                                   c.c_int, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+        L.flce_backward.restype = c.c_int
+        L.flce_backward.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
+                                    c.c_int64, c.c_int, c.c_int, c.c_float, c.c_void_p, c.c_void_p, c.c_void_p,
+                                    c.c_size_t, c.c_void_p]
+        L.flce_last_device_status.restype = c.c_int
+        L.flce_last_device_status.argtypes = [c.c_void_p, c.c_void_p, c.POINTER(c.c_int64)]
+        _lib = L
+    return _lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return int(x)
+
+
+def _stream(s):
+    if s is None:
+        return None
+    if hasattr(s, "cuda_stream"):
+        return s.cuda_stream
+    return int(s)
+
+
+def flce_version():
+    return lib().flce_version().decode()
+
+
+def flce_status_string(status):
+    return lib().flce_status_string(int(status)).decode()
+
+
+def flce_workspace_bytes(N, d, V, dt, for_backward):
+    return int(lib().flce_workspace_bytes(N, d, V, dt, int(bool(for_backward))))
+
+
+def flce_forward(H, W, targets, N, d, V, ignore_index, reduction, dt, loss_out, lse_out, workspace, workspace_bytes,
+                 hip_stream=None):
+    return lib().flce_forward(_ptr(H), _ptr(W), _ptr(targets), N, d, V, ignore_index, reduction, dt, _ptr(loss_out),
+                              _ptr(lse_out), _ptr(workspace), workspace_bytes, _stream(hip_stream))
+
+
+def flce_backward(H, W, targets, lse, N, d, V, ignore_index, reduction, dt, grad_loss, dH_out, dW_out, workspace,
+                  workspace_bytes, hip_stream=None):
+    return lib().flce_backward(_ptr(H), _ptr(W), _ptr(targets), _ptr(lse), N, d, V, ignore_index, reduction, dt,
+                               float(grad_loss), _ptr(dH_out), _ptr(dW_out), _ptr(workspace), workspace_bytes,
+                               _stream(hip_stream))
+
+
+def flce_last_device_status(workspace, hip_stream=None):
+    """Returns (status, n_valid)."""
+    nv = ctypes.c_int64(0)
+    st = lib().flce_last_device_status(_ptr(workspace), _stream(hip_stream), ctypes.byref(nv))
+    return st, nv.value

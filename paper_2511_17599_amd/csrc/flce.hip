@@ -1,0 +1,257 @@
+// C-ABI entry points of libflce (see include/flce.h): argument checks, the launch
+// plan (windows, chunks, workspace layout) and the launch sequences.  Host code
+// only; every step of the path runs in the kernels of kernels.h.
+#include "../../include/flce.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <mutex>
+
+#include "kernels.h"
+
+namespace flce {
+namespace {
+
+constexpr int64_t ALIGN = 256;
+constexpr int NUM_CU = 256;   // MI355X; the plan must not depend on a device query
+
+int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+int env_int(const char* name, int dflt, int lo, int hi) {
+  const char* s = std::getenv(name);
+  if (!s || !*s) return dflt;
+  long v = std::strtol(s, nullptr, 10);
+  if (v < lo) v = lo;
+  if (v > hi) v = hi;
+  return (int)v;
+}
+
+struct Plan {
+  int64_t N, d, V;
+  int esize;
+  int n_rb, n_vt;          // 256-row tiles of tokens / vocabulary
+  int64_t npad;
+  // forward
+  int n_win;
+  int64_t off_part, off_blk_loss, off_blk_cnt, off_blk_oor, fwd_bytes;
+  // backward
+  int n_vch, n_nch;        // chunks along vocabulary / tokens
+  int vc_tiles, nc_tiles;  // largest chunk, in tiles
+  int64_t off_HT, off_WT, off_G, off_GT, off_dHacc, off_dWacc, bwd_bytes;
+};
+
+bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
+  if (N <= 0 || d <= 0 || V <= 0 || (d % 8) != 0) return false;
+  if (N > 0x7FFFFF00ll || V > 0x7FFFFF00ll || d > (1 << 24)) return false;
+  if (dt != FLCE_DTYPE_BF16 && dt != FLCE_DTYPE_F32) return false;
+  p.N = N; p.d = d; p.V = V;
+  p.esize = dt == FLCE_DTYPE_BF16 ? 2 : 4;
+  p.n_rb = (int)ceil_div(N, TILE);
+  p.n_vt = (int)ceil_div(V, TILE);
+  p.npad = (int64_t)p.n_rb * TILE;
+
+  // Windows (Section 3.2.1): enough (row block, window) workgroups to cover the CUs.
+  int win = env_int("FLCE_WINDOWS", 0, 0, 1 << 16);
+  if (win == 0) win = p.n_rb >= NUM_CU ? 1 : (int)ceil_div(NUM_CU, p.n_rb);
+  if (win > p.n_vt) win = p.n_vt;
+  p.n_win = win;
+  int64_t o = ALIGN;                                  // header
+  p.off_part = o;       o = align_up(o + 3ll * win * p.npad * 4, ALIGN);
+  p.off_blk_loss = o;   o = align_up(o + (int64_t)p.n_rb * 4, ALIGN);
+  p.off_blk_cnt = o;    o = align_up(o + (int64_t)p.n_rb * 4, ALIGN);
+  p.off_blk_oor = o;    o = align_up(o + (int64_t)p.n_rb * 4, ALIGN);
+  p.fwd_bytes = o;
+
+  // Backward staging: a fixed-size G tile of at most vc x nc 256-tiles.
+  const int vc_max = env_int("FLCE_VC_TILES", 32, 1, 4096);
+  const int nc_max = env_int("FLCE_NC_TILES", 32, 1, 4096);
+  p.n_vch = (int)ceil_div(p.n_vt, vc_max);
+  p.n_nch = (int)ceil_div(p.n_rb, nc_max);
+  p.vc_tiles = (int)ceil_div(p.n_vt, p.n_vch);
+  p.nc_tiles = (int)ceil_div(p.n_rb, p.n_nch);
+  const int64_t vc_pad = (int64_t)p.vc_tiles * TILE, nc_pad = (int64_t)p.nc_tiles * TILE;
+  o = ALIGN;
+  p.off_HT = o;     o = align_up(o + d * p.npad * p.esize, ALIGN);
+  p.off_WT = o;     o = align_up(o + d * vc_pad * p.esize, ALIGN);
+  p.off_G = o;      o = align_up(o + nc_pad * vc_pad * p.esize, ALIGN);
+  p.off_GT = o;     o = align_up(o + nc_pad * vc_pad * p.esize, ALIGN);
+  p.off_dHacc = o;  if (p.n_vch > 1) o = align_up(o + N * d * 4, ALIGN);
+  p.off_dWacc = o;  if (p.n_nch > 1) o = align_up(o + vc_pad * d * 4, ALIGN);
+  p.bwd_bytes = o;
+  return true;
+}
+
+template <typename K>
+hipError_t allow_big_lds(K kernel) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             LDS_BYTES);
+}
+
+template <typename T>
+hipError_t prepare_kernels() {
+  hipError_t e;
+  if ((e = allow_big_lds(fwd_tiles_kernel<T>)) != hipSuccess) return e;
+  if ((e = allow_big_lds(recompute_kernel<T>)) != hipSuccess) return e;
+  if ((e = allow_big_lds(contract_kernel<T>)) != hipSuccess) return e;
+  return hipSuccess;
+}
+
+// The attribute is per device; set it on every call's current device (a cheap host-side call).
+template <typename T>
+flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t* y, int64_t ignore_index,
+                      int mean, float* loss_out, float* lse_out, char* ws, hipStream_t st) {
+  if (prepare_kernels<T>() != hipSuccess) return FLCE_ERR_HIP;
+  Header* hdr = reinterpret_cast<Header*>(ws);
+  float* part = reinterpret_cast<float*>(ws + p.off_part);
+  float* blk_loss = reinterpret_cast<float*>(ws + p.off_blk_loss);
+  int* blk_cnt = reinterpret_cast<int*>(ws + p.off_blk_cnt);
+  int* blk_oor = reinterpret_cast<int*>(ws + p.off_blk_oor);
+  const int grid = p.n_rb * p.n_win;
+  fwd_tiles_kernel<T><<<grid, THREADS, LDS_BYTES, st>>>(static_cast<const T*>(H), static_cast<const T*>(W), y,
+                                                        (int)p.N, (int)p.d, (int)p.V, ignore_index, p.n_rb, p.n_win,
+                                                        p.n_vt, part);
+  merge_rows_kernel<<<p.n_rb, 256, 0, st>>>(part, p.n_win, p.npad, y, (int)p.N, (int)p.V, ignore_index, lse_out,
+                                            blk_loss, blk_cnt, blk_oor);
+  finalize_loss_kernel<<<1, 256, 0, st>>>(blk_loss, blk_cnt, blk_oor, p.n_rb, mean, hdr, loss_out);
+  return hipGetLastError() == hipSuccess ? FLCE_OK : FLCE_ERR_HIP;
+}
+
+template <typename T, typename U>
+flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_t* y, const float* lse,
+                       int64_t ignore_index, int mean, float grad_loss, void* dH, void* dW, char* ws,
+                       hipStream_t st) {
+  if (prepare_kernels<T>() != hipSuccess) return FLCE_ERR_HIP;
+  const int N = (int)p.N, d = (int)p.d, V = (int)p.V;
+  Header* hdr = reinterpret_cast<Header*>(ws);
+  T* HT = reinterpret_cast<T*>(ws + p.off_HT);
+  T* WT = reinterpret_cast<T*>(ws + p.off_WT);
+  T* G = reinterpret_cast<T*>(ws + p.off_G);
+  T* GT = reinterpret_cast<T*>(ws + p.off_GT);
+  float* dHacc = reinterpret_cast<float*>(ws + p.off_dHacc);
+  float* dWacc = reinterpret_cast<float*>(ws + p.off_dWacc);
+  const int64_t vc_pad = (int64_t)p.vc_tiles * TILE, nc_pad = (int64_t)p.nc_tiles * TILE;
+  const int n_mt = (int)ceil_div(d, TILE);
+
+  scan_targets_kernel<<<1, 1024, 0, st>>>(y, N, V, ignore_index, hdr);
+  // H^T [d][npad]: K-contiguous operand of the dW contraction
+  transpose_pad_kernel<U><<<dim3((unsigned)ceil_div(p.npad, 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
+      static_cast<const U*>(H), d, N, 0, d, reinterpret_cast<U*>(HT), p.npad, (int)p.npad);
+
+  for (int vc = 0; vc < p.n_vch; ++vc) {
+    const int vt0 = (int)((int64_t)vc * p.n_vt / p.n_vch), vt1 = (int)((int64_t)(vc + 1) * p.n_vt / p.n_vch);
+    const int n_vt = vt1 - vt0;
+    // W^T chunk [d][vc_pad]: K-contiguous operand of the dH contraction
+    transpose_pad_kernel<U><<<dim3((unsigned)(n_vt * TILE / 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
+        static_cast<const U*>(W), d, V, vt0 * TILE, d, reinterpret_cast<U*>(WT), vc_pad, n_vt * TILE);
+    for (int nc = 0; nc < p.n_nch; ++nc) {
+      const int nt0 = (int)((int64_t)nc * p.n_rb / p.n_nch), nt1 = (int)((int64_t)(nc + 1) * p.n_rb / p.n_nch);
+      const int n_nt = nt1 - nt0;
+      recompute_kernel<T><<<n_nt * n_vt, THREADS, LDS_BYTES, st>>>(
+          static_cast<const T*>(H), static_cast<const T*>(W), y, lse, N, d, V, ignore_index, nt0, n_nt, vt0, n_vt, G,
+          vc_pad, GT, nc_pad);
+      // dW[vocab chunk] += GT . H^T[:, token chunk]^T   (contraction over the token chunk)
+      {
+        int flags = 0;
+        if (nc > 0) flags |= READ_ACC;
+        flags |= (nc + 1 < p.n_nch) ? WRITE_ACC : WRITE_OUT;
+        contract_kernel<T><<<n_vt * n_mt, THREADS, LDS_BYTES, st>>>(
+            HT + (int64_t)nt0 * TILE, p.npad, d, GT, nc_pad, n_vt * TILE, n_nt * TILE, n_mt, n_vt, dWacc,
+            vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags, hdr, grad_loss, mean);
+      }
+      // dH[token chunk] += G . W^T[:, vocab chunk]^T    (contraction over the vocabulary chunk)
+      {
+        int flags = 0;
+        if (vc > 0) flags |= READ_ACC;
+        flags |= (vc + 1 < p.n_vch) ? WRITE_ACC : WRITE_OUT;
+        contract_kernel<T><<<n_nt * n_mt, THREADS, LDS_BYTES, st>>>(
+            WT, vc_pad, d, G, vc_pad, n_nt * TILE, n_vt * TILE, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH),
+            nt0 * TILE, N, flags, hdr, grad_loss, mean);
+      }
+    }
+  }
+  return hipGetLastError() == hipSuccess ? FLCE_OK : FLCE_ERR_HIP;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+}  // namespace flce
+
+extern "C" {
+
+const char* flce_version(void) { return "0.1.0"; }
+
+const char* flce_status_string(flce_status s) {
+  switch (s) {
+    case FLCE_OK: return "ok";
+    case FLCE_ERR_BAD_ARG: return "bad argument";
+    case FLCE_ERR_BAD_SHAPE: return "bad shape";
+    case FLCE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case FLCE_ERR_TARGET_RANGE: return "target outside [0, V)";
+    case FLCE_ERR_UNSUPPORTED: return "unsupported";
+    case FLCE_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+size_t flce_workspace_bytes(int64_t N, int64_t d, int64_t V, flce_dtype dt, int for_backward) {
+  flce::Plan p;
+  if (!flce::make_plan(N, d, V, dt, p)) return 0;
+  return (size_t)(for_backward ? p.bwd_bytes : p.fwd_bytes);
+}
+
+flce_status flce_forward(const void* H, const void* W, const int64_t* targets, int64_t N, int64_t d, int64_t V,
+                         int64_t ignore_index, flce_reduction reduction, flce_dtype dt, float* loss_out,
+                         float* lse_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!H || !W || !targets || !loss_out || !lse_out) return FLCE_ERR_BAD_ARG;
+  if (reduction != FLCE_REDUCE_MEAN && reduction != FLCE_REDUCE_SUM) return FLCE_ERR_BAD_ARG;
+  if (dt != FLCE_DTYPE_BF16 && dt != FLCE_DTYPE_F32) return FLCE_ERR_BAD_ARG;
+  flce::Plan p;
+  if (!flce::make_plan(N, d, V, dt, p)) return FLCE_ERR_BAD_SHAPE;
+  if (!flce::aligned16(H) || !flce::aligned16(W)) return FLCE_ERR_BAD_ARG;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < (size_t)p.fwd_bytes)
+    return FLCE_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int mean = reduction == FLCE_REDUCE_MEAN;
+  char* ws = static_cast<char*>(workspace);
+  if (dt == FLCE_DTYPE_BF16)
+    return flce::forward_t<flce::bf16_t>(p, H, W, targets, ignore_index, mean, loss_out, lse_out, ws, st);
+  return flce::forward_t<float>(p, H, W, targets, ignore_index, mean, loss_out, lse_out, ws, st);
+}
+
+flce_status flce_backward(const void* H, const void* W, const int64_t* targets, const float* lse, int64_t N,
+                          int64_t d, int64_t V, int64_t ignore_index, flce_reduction reduction, flce_dtype dt,
+                          float grad_loss, void* dH_out, void* dW_out, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  if (!H || !W || !targets || !lse || !dH_out || !dW_out) return FLCE_ERR_BAD_ARG;
+  if (reduction != FLCE_REDUCE_MEAN && reduction != FLCE_REDUCE_SUM) return FLCE_ERR_BAD_ARG;
+  if (dt != FLCE_DTYPE_BF16 && dt != FLCE_DTYPE_F32) return FLCE_ERR_BAD_ARG;
+  flce::Plan p;
+  if (!flce::make_plan(N, d, V, dt, p)) return FLCE_ERR_BAD_SHAPE;
+  if (!flce::aligned16(H) || !flce::aligned16(W) || !flce::aligned16(dH_out) || !flce::aligned16(dW_out))
+    return FLCE_ERR_BAD_ARG;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < (size_t)p.bwd_bytes)
+    return FLCE_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int mean = reduction == FLCE_REDUCE_MEAN;
+  char* ws = static_cast<char*>(workspace);
+  if (dt == FLCE_DTYPE_BF16)
+    return flce::backward_t<flce::bf16_t, uint16_t>(p, H, W, targets, lse, ignore_index, mean, grad_loss, dH_out,
+                                                    dW_out, ws, st);
+  return flce::backward_t<float, uint32_t>(p, H, W, targets, lse, ignore_index, mean, grad_loss, dH_out, dW_out, ws,
+                                           st);
+}
+
+flce_status flce_last_device_status(const void* workspace, void* hip_stream, int64_t* n_valid_out) {
+  if (!workspace) return FLCE_ERR_BAD_ARG;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  flce::Header h;
+  if (hipStreamSynchronize(st) != hipSuccess) return FLCE_ERR_HIP;
+  if (hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return FLCE_ERR_HIP;
+  if (n_valid_out) *n_valid_out = h.n_valid;
+  return h.status == 0 ? FLCE_OK : FLCE_ERR_TARGET_RANGE;
+}
+
+}  // extern "C"

@@ -1,0 +1,420 @@
+// Device kernels of the fused projection + cross-entropy path.
+//
+//   forward : fwd_tiles_kernel  (logit tiles on MFMA, online max / sum-exp and target
+//             gather per lane: Alg. 1 in tile form; one workgroup per row block x
+//             vocabulary window: Section 3.2.1)
+//             merge_rows_kernel + finalize_loss_kernel (the merging epilogue of
+//             Section 3.2.1, lse = m + ln a, per-row loss, fixed-order sums)
+//   backward: scan_targets_kernel (n_valid, range flag)
+//             transpose_pad_kernel (K-contiguous copies of H and W for the two
+//             gradient contractions)
+//             recompute_kernel (Alg. 2: z recomputed, g = p - onehot, written once to
+//             a fixed-size staging tile in both orientations)
+//             contract_kernel (Eq. 4 and Eq. 5 as output-stationary MFMA
+//             contractions with a fixed chunk order; Gamma applied at the flush)
+#pragma once
+#include "tile_mma.h"
+
+namespace flce {
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float NEG_INF = -__builtin_inff();
+
+// First 256 bytes of every workspace.
+struct Header {
+  int32_t status;      // 0 or FLCE_ERR_TARGET_RANGE
+  int32_t pad0;
+  int64_t n_valid;     // number of counted rows
+  float loss_sum;      // un-normalised sum of per-row losses (forward only)
+  float pad1;
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Classifies one target: returns its id when the row counts, -1 otherwise, and
+// reports a counted id outside [0, V) through `oor`.
+__device__ __forceinline__ int classify_target(int64_t y, int64_t ignore_index, int V, bool& oor) {
+  oor = false;
+  if (y == ignore_index) return -1;
+  if (y < 0 || y >= (int64_t)V) { oor = true; return -1; }
+  return (int)y;
+}
+
+// Merge of safe-softmax partials (m_k, a_k) in slot order; slots with a == 0 are
+// the identity.  Returns (M, A) with A relative to M.
+template <int S>
+__device__ __forceinline__ void merge_fixed(const float (&m)[S], const float (&a)[S], float& M, float& A) {
+  M = NEG_INF;
+#pragma unroll
+  for (int s = 0; s < S; ++s) if (a[s] > 0.f) M = fmaxf(M, m[s]);
+  A = 0.f;
+#pragma unroll
+  for (int s = 0; s < S; ++s) if (a[s] > 0.f) A += a[s] * fast_exp2((m[s] - M) * LOG2E);
+}
+
+// ------------------------------------------------------------------------------------
+// Forward tiles.  A = W tile (M = vocabulary, inside a lane), B = H tile (N = tokens,
+// across lanes): each lane streams the logits of its own token columns and keeps
+// (m, a, z_target) in registers across the vocabulary tiles of its window.
+// part = [3][n_win][n_rb * 256] floats: m, a, z_target per (window, row).
+// ------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(THREADS) void fwd_tiles_kernel(
+    const T* __restrict__ H, const T* __restrict__ W, const int64_t* __restrict__ y,
+    int N, int d, int V, int64_t ignore_index, int n_rb, int n_win, int n_vt, float* __restrict__ part) {
+  extern __shared__ __align__(16) char lds[];
+  const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  int rb, win;
+  grouped_raster(id, n_rb, n_win, 8, rb, win);
+  const int vt_begin = (int)((int64_t)win * n_vt / n_win);
+  const int vt_end = (int)((int64_t)(win + 1) * n_vt / n_win);
+  const int n0 = rb * TILE;
+  const int64_t ld_bytes = (int64_t)d * sizeof(T);
+
+  int tgt[WN];
+  float m[WN], a[WN], zt[WN];
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int n = n0 + tile_n(j);
+    bool oor;
+    tgt[j] = (n < N) ? classify_target(y[n], ignore_index, V, oor) : -1;
+    m[j] = NEG_INF; a[j] = 0.f; zt[j] = 0.f;
+  }
+
+  const TileSrc Bsrc{reinterpret_cast<const char*>(H), ld_bytes, n0, N};
+  f32x16 acc[WM][WN];
+  for (int vt = vt_begin; vt < vt_end; ++vt) {
+    const int v0 = vt * TILE;
+    const TileSrc Asrc{reinterpret_cast<const char*>(W), ld_bytes, v0, V};
+    tile_mainloop<T>(Asrc, Bsrc, (int)ld_bytes, lds, acc);
+
+    if (v0 + TILE > V) {       // ragged last vocabulary tile: padded logits are -inf
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (v0 + tile_m(i, r) >= V) {
+#pragma unroll
+            for (int j = 0; j < WN; ++j) acc[i][j][r] = NEG_INF;
+          }
+    }
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+      float tmax = NEG_INF;
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, acc[i][j][r]);
+      const float mn = fmaxf(m[j], tmax);
+      const float ms = (mn == NEG_INF) ? 0.f : mn;     // all-padded slice: keep exp arguments finite
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += fast_exp2((acc[i][j][r] - ms) * LOG2E);
+      a[j] = a[j] * fast_exp2((m[j] - ms) * LOG2E) + sum;
+      m[j] = mn;
+
+      const int rel = tgt[j] - v0;
+      const bool mine = (unsigned)rel < (unsigned)TILE && tgt[j] >= 0;
+      if (__ballot(mine) != 0ull) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (mine && tile_m(i, r) == rel) zt[j] = acc[i][j][r];
+      }
+    }
+  }
+
+  // Four lanes hold partial state of each token (2 M-wavefronts x 2 lane halves):
+  // merge them in fixed slot order through LDS (free after the main loop's barrier).
+  float* sm = reinterpret_cast<float*>(lds);
+  float* sa = sm + 4 * TILE;
+  float* sz = sa + 4 * TILE;
+  {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int slot = (wave >> 2) * 2 + (lane >> 5);
+#pragma unroll
+    for (int j = 0; j < WN; ++j) {
+      const int tok = tile_n(j);
+      sm[slot * TILE + tok] = m[j];
+      sa[slot * TILE + tok] = a[j];
+      sz[slot * TILE + tok] = zt[j];
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < TILE) {
+    const int tok = threadIdx.x;
+    float pm[4], pa[4];
+    float z = 0.f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) { pm[s] = sm[s * TILE + tok]; pa[s] = sa[s * TILE + tok]; z += sz[s * TILE + tok]; }
+    float M, A;
+    merge_fixed<4>(pm, pa, M, A);
+    const int64_t npad = (int64_t)n_rb * TILE;
+    const int64_t o = (int64_t)win * npad + n0 + tok;
+    part[o] = M;
+    part[(int64_t)n_win * npad + o] = A;
+    part[2 * (int64_t)n_win * npad + o] = z;
+  }
+}
+
+// Deterministic block sum of 256 values (fixed tree).
+__device__ __forceinline__ float block_sum_256(float v, float* sh) {
+  sh[threadIdx.x] = v;
+  __syncthreads();
+#pragma unroll
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+    __syncthreads();
+  }
+  float r = sh[0];
+  __syncthreads();
+  return r;
+}
+
+// One thread per row: merge the window partials in window order, lse = M + ln A,
+// loss_i = lse - z_target for counted rows; per-block sums in a fixed tree.
+__global__ __launch_bounds__(256) void merge_rows_kernel(
+    const float* __restrict__ part, int n_win, int64_t npad, const int64_t* __restrict__ y, int N, int V,
+    int64_t ignore_index, float* __restrict__ lse_out, float* __restrict__ blk_loss, int* __restrict__ blk_cnt,
+    int* __restrict__ blk_oor) {
+  __shared__ float sh[256];
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  float loss = 0.f, cnt = 0.f, bad = 0.f;
+  if (n < N) {
+    float M = NEG_INF;
+    for (int w = 0; w < n_win; ++w) {
+      const float aw = part[(int64_t)n_win * npad + (int64_t)w * npad + n];
+      if (aw > 0.f) M = fmaxf(M, part[(int64_t)w * npad + n]);
+    }
+    float A = 0.f, z = 0.f;
+    for (int w = 0; w < n_win; ++w) {
+      const float mw = part[(int64_t)w * npad + n];
+      const float aw = part[(int64_t)n_win * npad + (int64_t)w * npad + n];
+      if (aw > 0.f) A += aw * fast_exp2((mw - M) * LOG2E);
+      z += part[2 * (int64_t)n_win * npad + (int64_t)w * npad + n];
+    }
+    const float lse = M + logf(A);
+    lse_out[n] = lse;
+    bool oor;
+    const int t = classify_target(y[n], ignore_index, V, oor);
+    if (t >= 0) { loss = lse - z; cnt = 1.f; }
+    if (oor) bad = 1.f;
+  }
+  const float bl = block_sum_256(loss, sh);
+  const float bc = block_sum_256(cnt, sh);     // <= 256: exact in fp32
+  const float bb = block_sum_256(bad, sh);
+  if (threadIdx.x == 0) {
+    blk_loss[blockIdx.x] = bl;
+    blk_cnt[blockIdx.x] = (int)bc;
+    blk_oor[blockIdx.x] = bb > 0.f ? 1 : 0;
+  }
+}
+
+// One block: fixed-order fp64 sum of the per-block partials, normalisation, header.
+__global__ __launch_bounds__(256) void finalize_loss_kernel(
+    const float* __restrict__ blk_loss, const int* __restrict__ blk_cnt, const int* __restrict__ blk_oor, int n_blk,
+    int mean, Header* __restrict__ hdr, float* __restrict__ loss_out) {
+  __shared__ double sl[256];
+  __shared__ long long sc[256];
+  __shared__ int so[256];
+  double l = 0.0; long long c = 0; int o = 0;
+  for (int b = threadIdx.x; b < n_blk; b += 256) { l += (double)blk_loss[b]; c += blk_cnt[b]; o |= blk_oor[b]; }
+  sl[threadIdx.x] = l; sc[threadIdx.x] = c; so[threadIdx.x] = o;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) {
+      sl[threadIdx.x] += sl[threadIdx.x + s];
+      sc[threadIdx.x] += sc[threadIdx.x + s];
+      so[threadIdx.x] |= so[threadIdx.x + s];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double total = sl[0];
+    const long long nv = sc[0];
+    double loss = total;
+    if (mean) loss = nv > 0 ? total / (double)nv : 0.0;
+    hdr->status = so[0] ? 4 : 0;
+    hdr->pad0 = 0;
+    hdr->n_valid = nv;
+    hdr->loss_sum = (float)total;
+    hdr->pad1 = 0.f;
+    *loss_out = (float)loss;
+  }
+}
+
+// Backward's integer pass over the targets: n_valid and the range flag (exact).
+__global__ __launch_bounds__(1024) void scan_targets_kernel(const int64_t* __restrict__ y, int N, int V,
+                                                            int64_t ignore_index, Header* __restrict__ hdr) {
+  __shared__ int sc[1024];
+  __shared__ int so[1024];
+  int c = 0, o = 0;
+  for (int n = threadIdx.x; n < N; n += 1024) {
+    bool oor;
+    if (classify_target(y[n], ignore_index, V, oor) >= 0) ++c;
+    o |= oor ? 1 : 0;
+  }
+  sc[threadIdx.x] = c; so[threadIdx.x] = o;
+  __syncthreads();
+  for (int s = 512; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) { sc[threadIdx.x] += sc[threadIdx.x + s]; so[threadIdx.x] |= so[threadIdx.x + s]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    hdr->status = so[0] ? 4 : 0;
+    hdr->pad0 = 0;
+    hdr->n_valid = sc[0];
+    hdr->loss_sum = 0.f;
+    hdr->pad1 = 0.f;
+  }
+}
+
+// dst[c][r] = src[r0 + r][c]  for c < cols, r < rows_pad; zero where r0 + r >= rows_total.
+// U is an unsigned integer type of the element's width (pure data movement).
+template <typename U>
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const U* __restrict__ src, int64_t ld_src, int rows_total,
+                                                            int r0, int cols, U* __restrict__ dst, int64_t ld_dst,
+                                                            int rows_pad) {
+  __shared__ U tile[64][65];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int rb = blockIdx.x * 64, cb = blockIdx.y * 64;
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const int r = rb + ty + 4 * k, c = cb + tx;
+    U v = 0;
+    if (r < rows_pad && r0 + r < rows_total && c < cols) v = src[(int64_t)(r0 + r) * ld_src + c];
+    tile[ty + 4 * k][tx] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const int c = cb + ty + 4 * k, r = rb + tx;
+    if (c < cols && r < rows_pad) dst[(int64_t)c * ld_dst + r] = tile[tx][ty + 4 * k];
+  }
+}
+
+template <typename T> struct Pack4;
+template <> struct Pack4<float> {
+  static __device__ __forceinline__ void store(float* p, float a, float b, float c, float d) {
+    *reinterpret_cast<f32x4*>(p) = f32x4{a, b, c, d};
+  }
+  static __device__ __forceinline__ float one(float v) { return v; }
+};
+template <> struct Pack4<bf16_t> {
+  static __device__ __forceinline__ void store(bf16_t* p, float a, float b, float c, float d) {
+    uint2 v;
+    v.x = (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
+    v.y = (uint32_t)f32_to_bf16_bits(c) | ((uint32_t)f32_to_bf16_bits(d) << 16);
+    *reinterpret_cast<uint2*>(p) = v;
+  }
+  static __device__ __forceinline__ bf16_t one(float v) { return bf16_t{f32_to_bf16_bits(v)}; }
+};
+
+// ------------------------------------------------------------------------------------
+// Backward, step 1: logit tile recomputed exactly as in the forward, then
+//   g = counted_row ? exp(z - lse_row) - [v == y_row] : 0      (unscaled; Gamma comes later)
+// rounded to T and written to the staging tile in both orientations:
+//   G [token - chunk_n0][vocab - chunk_v0]   (ldG  elements per row)
+//   GT[vocab - chunk_v0][token - chunk_n0]   (ldGT elements per row)
+// Padded vocabulary columns and padded / ignored token rows are written as 0.
+// ------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(THREADS) void recompute_kernel(
+    const T* __restrict__ H, const T* __restrict__ W, const int64_t* __restrict__ y, const float* __restrict__ lse,
+    int N, int d, int V, int64_t ignore_index, int nt0, int n_nt, int vt0, int n_vt,
+    T* __restrict__ G, int64_t ldG, T* __restrict__ GT, int64_t ldGT) {
+  extern __shared__ __align__(16) char lds[];
+  const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  int p, q;                                    // token tile, vocabulary tile inside the chunk
+  grouped_raster(id, n_nt, n_vt, 8, p, q);
+  const int n0 = (nt0 + p) * TILE, v0 = (vt0 + q) * TILE;
+  const int64_t ld_bytes = (int64_t)d * sizeof(T);
+  const TileSrc Asrc{reinterpret_cast<const char*>(W), ld_bytes, v0, V};
+  const TileSrc Bsrc{reinterpret_cast<const char*>(H), ld_bytes, n0, N};
+  f32x16 acc[WM][WN];
+  tile_mainloop<T>(Asrc, Bsrc, (int)ld_bytes, lds, acc);
+
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int nl = p * TILE + tile_n(j);       // row inside the staging tile
+    const int n = n0 + tile_n(j);
+    bool oor;
+    const int tgt = (n < N) ? classify_target(y[n], ignore_index, V, oor) : -1;
+    const bool counted = tgt >= 0;
+    const float l = (n < N) ? lse[n] : 0.f;
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int mloc = tile_m(i, rq * 4);    // first of 4 consecutive vocabulary positions
+        float g[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int v = v0 + mloc + e;
+          float pz = fast_exp2((acc[i][j][rq * 4 + e] - l) * LOG2E) - ((v == tgt) ? 1.f : 0.f);
+          g[e] = (counted && v < V) ? pz : 0.f;
+        }
+        const int vl = q * TILE + mloc;
+        Pack4<T>::store(G + (int64_t)nl * ldG + vl, g[0], g[1], g[2], g[3]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) GT[(int64_t)(vl + e) * ldGT + nl] = Pack4<T>::one(g[e]);
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Backward, step 2: out[n][m] (+)= sum_k A[m][k] * B[n][k]
+//   dH: A = W^T chunk [d][Vc], B = G  [tokens][Vc]  (contraction over the vocabulary chunk)
+//   dW: A = H^T       [d][Nc], B = GT [vocab][Nc]   (contraction over the token chunk)
+// M = hidden index, so each lane owns 4 consecutive output elements of one row.
+// Chunks are accumulated in fp32 in a fixed order: READ_ACC adds the running sum,
+// WRITE_ACC stores it back, WRITE_OUT multiplies by Gamma and rounds to T.
+// ------------------------------------------------------------------------------------
+enum : int { READ_ACC = 1, WRITE_ACC = 2, WRITE_OUT = 4 };
+
+template <typename T>
+__global__ __launch_bounds__(THREADS) void contract_kernel(
+    const T* __restrict__ A, int64_t lda, int d, const T* __restrict__ B, int64_t ldb, int b_rows, int k_elems,
+    int n_mt, int n_nt, float* __restrict__ accbuf, int acc_row0, T* __restrict__ out, int out_row0, int out_rows,
+    int flags, const Header* __restrict__ hdr, float grad_loss, int mean) {
+  extern __shared__ __align__(16) char lds[];
+  const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  int p, q;                                    // output-row tile, hidden tile
+  grouped_raster(id, n_nt, n_mt, 8, p, q);
+  const TileSrc Asrc{reinterpret_cast<const char*>(A), lda * (int64_t)sizeof(T), q * TILE, d};
+  const TileSrc Bsrc{reinterpret_cast<const char*>(B), ldb * (int64_t)sizeof(T), p * TILE, b_rows};
+  f32x16 acc[WM][WN];
+  tile_mainloop<T>(Asrc, Bsrc, k_elems * (int)sizeof(T), lds, acc);
+
+  float scale = grad_loss;
+  if (mean) {
+    const int64_t nv = hdr->n_valid;
+    scale = nv > 0 ? grad_loss / (float)nv : 0.f;
+  }
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    const int n = out_row0 + p * TILE + tile_n(j);
+    if (n >= out_rows) continue;
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int m = q * TILE + tile_m(i, rq * 4);
+        if (m >= d) continue;
+        f32x4 v = {acc[i][j][rq * 4], acc[i][j][rq * 4 + 1], acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]};
+        float* ap = accbuf + (int64_t)(n - acc_row0) * d + m;
+        if (flags & READ_ACC) v += *reinterpret_cast<const f32x4*>(ap);
+        if (flags & WRITE_ACC) *reinterpret_cast<f32x4*>(ap) = v;
+        if (flags & WRITE_OUT) {
+          // "+ 0.f" turns a -0 product into +0 so untouched rows come out as +0
+          Pack4<T>::store(out + (int64_t)n * d + m, v[0] * scale + 0.f, v[1] * scale + 0.f, v[2] * scale + 0.f,
+                          v[3] * scale + 0.f);
+        }
+      }
+  }
+}
+
+}  // namespace flce

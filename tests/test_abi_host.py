@@ -1,0 +1,74 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header
+declares, sizes its workspace without an N*V term, and rejects bad arguments before
+touching any device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2511_17599_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "flce.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(flce_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert set(names) == set(B.EXPORTS)
+    L = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+    assert re.fullmatch(r"\d+\.\d+\.\d+", B.flce_version())
+    assert B.flce_status_string(B.FLCE_OK) == "ok"
+    assert "target" in B.flce_status_string(B.FLCE_ERR_TARGET_RANGE)
+
+
+def test_workspace_has_no_NV_term():
+    for dt in (B.FLCE_DTYPE_BF16, B.FLCE_DTYPE_F32):
+        for bwd in (0, 1):
+            base = B.flce_workspace_bytes(8192, 4096, 128256, dt, bwd)
+            assert base > 0
+            # doubling N and V together would quadruple an N*V term; the workspace at most ~doubles
+            big = B.flce_workspace_bytes(16384, 4096, 256512, dt, bwd)
+            assert big <= 2.2 * base + (1 << 20)
+    # the long-sequence shape: naive fp32 logits are 67 GB, the workspace stays far below that
+    ws = B.flce_workspace_bytes(131072, 4096, 128256, B.FLCE_DTYPE_BF16, 1)
+    assert ws < 0.1 * 131072 * 128256 * 4
+    fw = B.flce_workspace_bytes(131072, 4096, 128256, B.FLCE_DTYPE_BF16, 0)
+    assert fw < 64 * (1 << 20)
+
+
+@pytest.mark.parametrize("N,d,V", [(0, 64, 64), (64, 0, 64), (64, 64, 0), (64, 60, 64), (-1, 64, 64)])
+def test_bad_shapes_are_rejected(N, d, V):
+    assert B.flce_workspace_bytes(N, d, V, B.FLCE_DTYPE_BF16, 0) == 0
+    st = B.flce_forward(256, 256, 256, N, d, V, -100, B.FLCE_REDUCE_MEAN, B.FLCE_DTYPE_BF16, 256, 256, 256, 1 << 30)
+    assert st == B.FLCE_ERR_BAD_SHAPE
+
+
+def test_bad_arguments_are_rejected_without_a_device():
+    ok = dict(N=256, d=64, V=512)
+    need_f = B.flce_workspace_bytes(256, 64, 512, B.FLCE_DTYPE_F32, 0)
+    need_b = B.flce_workspace_bytes(256, 64, 512, B.FLCE_DTYPE_F32, 1)
+    p = 4096  # a fake, aligned, never dereferenced device address
+    f = lambda **kw: B.flce_forward(kw.get("H", p), p, p, ok["N"], ok["d"], ok["V"], -100,
+                                    kw.get("red", B.FLCE_REDUCE_MEAN), kw.get("dt", B.FLCE_DTYPE_F32), p, p,
+                                    kw.get("ws", p), kw.get("wsb", need_f))
+    assert f(H=None) == B.FLCE_ERR_BAD_ARG
+    assert f(H=p + 4) == B.FLCE_ERR_BAD_ARG                 # misaligned tensor
+    assert f(red=2) == B.FLCE_ERR_BAD_ARG
+    assert f(dt=7) == B.FLCE_ERR_BAD_ARG
+    assert f(ws=None) == B.FLCE_ERR_WORKSPACE
+    assert f(ws=p + 16) == B.FLCE_ERR_WORKSPACE             # misaligned workspace
+    assert f(wsb=need_f - 1) == B.FLCE_ERR_WORKSPACE
+    b = lambda **kw: B.flce_backward(p, p, p, kw.get("lse", p), 256, 64, 512, -100, B.FLCE_REDUCE_SUM,
+                                     B.FLCE_DTYPE_F32, 1.0, p, kw.get("dW", p), p, kw.get("wsb", need_b))
+    assert b(lse=None) == B.FLCE_ERR_BAD_ARG
+    assert b(dW=None) == B.FLCE_ERR_BAD_ARG
+    assert b(wsb=need_b - 1) == B.FLCE_ERR_WORKSPACE
+    assert B.lib().flce_last_device_status(None, None, None) == B.FLCE_ERR_BAD_ARG

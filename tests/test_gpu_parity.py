@@ -1,0 +1,166 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU fp64 oracle on
+the same seeded inputs, element by element.
+
+Tolerances (fixed by the benchmark definition): loss 1e-5 relative (fp32) / 2e-3
+(bf16); dH and dW max|x - ref| / max|ref| <= 1e-4 (fp32) / 2e-2 (bf16); n_valid, the
+ignore mask (rows of dH that are exactly +0) and target indexing bit-exact.
+"""
+import os
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import flce_oracle as O                       # noqa: E402
+from paper_2511_17599_amd import binding as B             # noqa: E402
+from paper_2511_17599_amd import inputs as I              # noqa: E402
+from paper_2511_17599_amd.runner import run_workload      # noqa: E402
+
+TOL = {"f32": dict(loss=1e-5, grad=1e-4, lse=2e-6), "bf16": dict(loss=2e-3, grad=2e-2, lse=2e-3)}
+
+
+@pytest.fixture(autouse=True)
+def _need_gpu_and_clean_env(monkeypatch):
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    for k in ("FLCE_WINDOWS", "FLCE_VC_TILES", "FLCE_NC_TILES"):
+        monkeypatch.delenv(k, raising=False)
+    yield
+
+
+def nerr(got, ref):
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300))
+
+
+def check_against_oracle(wl, x, grad_loss=1.0, expect_status=B.FLCE_OK):
+    print(f"[case] {wl.name} N={wl.N} d={wl.d} V={wl.V} {wl.dtype} {wl.reduction} seed={wl.seed}", flush=True)
+    got = run_workload(wl, x, grad_loss=grad_loss)
+    Hd, Wd = I.to_f64(x["H"]), I.to_f64(x["W"])
+    f = O.forward(Hd, Wd, x["y"], wl.ignore_index, wl.reduction)
+    b = O.backward(Hd, Wd, x["y"], wl.ignore_index, wl.reduction, grad_loss)
+    tol = TOL[wl.dtype]
+    assert got["status"] == expect_status
+    assert got["n_valid"] == f["n_valid"] == got["n_valid_bwd"]
+    assert np.all(np.isfinite(got["lse"]))
+    lse_err = np.abs(got["lse"] - f["lse"]).max() / np.abs(f["lse"]).max()
+    assert lse_err <= tol["lse"], lse_err
+    assert abs(got["loss"] - f["loss"]) <= tol["loss"] * max(abs(f["loss"]), 1e-30), (got["loss"], f["loss"])
+    # rows that do not count: dH exactly +0, bit for bit
+    dead = ~f["valid"]
+    s = got["session"]
+    if dead.any():
+        raw = s.dH.view(torch.int16 if wl.dtype == "bf16" else torch.int32).cpu().numpy()
+        assert not raw[dead].any()
+    if f["n_valid"] > 0:
+        eH, eW = nerr(got["dH"], b["dH"]), nerr(got["dW"], b["dW"])
+        print(f"       loss {got['loss']:.7g} vs {f['loss']:.7g}  lse_err {lse_err:.2e}  dH {eH:.2e}  dW {eW:.2e}",
+              flush=True)
+        assert eH <= tol["grad"], eH
+        assert eW <= tol["grad"], eW
+    else:
+        assert not got["dH"].any() and not got["dW"].any() and got["loss"] == 0.0
+    return got, f, b
+
+
+def custom(name, N, d, V, dtype, seed, targets="uniform", ignore_frac=0.0, reduction="mean", w_std=0.02, zipf_s=1.1):
+    return I.Workload(name, N, d, V, dtype, targets, zipf_s=zipf_s, ignore_frac=ignore_frac, reduction=reduction,
+                      seed=seed, w_std=w_std)
+
+
+def test_tiny_f32_workload():
+    wl = I.WORKLOADS["tiny_f32"]
+    check_against_oracle(wl, I.make_inputs(wl))
+
+
+@pytest.mark.parametrize("wl", [
+    custom("bf16_ragged", 600, 200, 1000, "bf16", 11, ignore_frac=0.1),
+    custom("f32_ragged", 300, 72, 777, "f32", 12, ignore_frac=0.2, reduction="sum"),
+    custom("bf16_one_tile", 256, 64, 256, "bf16", 13),
+    custom("bf16_small_everything", 5, 8, 3, "bf16", 14),
+    custom("f32_single_row", 1, 8, 1, "f32", 15),
+    custom("bf16_zipf_sum", 1030, 256, 2049, "bf16", 16, targets="zipf", reduction="sum"),
+], ids=lambda w: w.name)
+def test_ragged_and_small_shapes(wl):
+    check_against_oracle(wl, I.make_inputs(wl), grad_loss=1.0 if wl.reduction == "mean" else -0.75)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("windows,vc,nc", [(1, 1, 1), (3, 2, 1), (5, 1, 2), (64, 3, 3)])
+def test_chunk_and_window_splits(monkeypatch, dtype, windows, vc, nc):
+    """Forces several vocabulary windows in the forward and several vocabulary / token chunks in
+    the backward on a small problem, so the merge and the fixed-order accumulation are exercised."""
+    monkeypatch.setenv("FLCE_WINDOWS", str(windows))
+    monkeypatch.setenv("FLCE_VC_TILES", str(vc))
+    monkeypatch.setenv("FLCE_NC_TILES", str(nc))
+    wl = custom(f"split_{dtype}_{windows}_{vc}_{nc}", 700, 136, 1500, dtype, 21, ignore_frac=0.05)
+    check_against_oracle(wl, I.make_inputs(wl))
+
+
+@pytest.mark.parametrize("dtype,w_std", [("bf16", 1.0), ("f32", 0.5)])
+def test_peaked_softmax_large_logits(dtype, w_std):
+    """Logits with a standard deviation of tens: exercises the max shift of the online softmax."""
+    wl = custom(f"peaked_{dtype}", 512, 1024, 3000, dtype, 31, ignore_frac=0.03, w_std=w_std)
+    check_against_oracle(wl, I.make_inputs(wl))
+
+
+def test_target_positions_and_mask_are_exact():
+    """Targets on tile edges, first / last id, a hot id, and ignored rows in between."""
+    V, N, d = 777, 520, 64
+    wl = custom("edges", N, d, V, "f32", 41)
+    x = I.make_inputs(wl)
+    y = np.full(N, 3, dtype=np.int64)                       # hot id
+    special = [0, 255, 256, 511, 512, 767, 768, 776, 1, 254, 257]
+    y[:len(special)] = special
+    y[100:140] = wl.ignore_index
+    y[255:258] = [776, wl.ignore_index, 0]                  # across a row-tile edge
+    x["y"] = y
+    got, f, b = check_against_oracle(wl, x)
+    # W = 0 makes G exactly Gamma * (1/V - onehot): the -Gamma term must sit on row y_i of dW
+    x0 = dict(x, W=np.zeros_like(x["W"]))
+    got0, f0, b0 = check_against_oracle(custom("edges_w0", N, d, V, "f32", 41), x0)
+    np.testing.assert_allclose(got0["lse"], np.log(V), rtol=1e-6)
+    assert not got0["dH"].any()
+
+
+def test_all_rows_ignored():
+    wl = custom("all_ignored", 300, 64, 500, "bf16", 51)
+    x = I.make_inputs(wl)
+    x["y"][:] = wl.ignore_index
+    for red in ("mean", "sum"):
+        w2 = custom("all_ignored_" + red, 300, 64, 500, "bf16", 51, reduction=red)
+        got, f, _ = check_against_oracle(w2, x)
+        assert got["loss"] == 0.0 and got["n_valid"] == 0
+
+
+def test_ignore_index_inside_vocabulary():
+    wl = I.Workload("ignore_in_range", 400, 64, 300, "f32", "uniform", seed=52, ignore_index=7)
+    x = I.make_inputs(wl)
+    x["y"][::5] = 7
+    check_against_oracle(wl, x)
+
+
+def test_out_of_range_target_is_flagged_and_dropped():
+    wl = custom("oor", 300, 64, 500, "f32", 53)
+    x = I.make_inputs(wl)
+    x["y"][17] = 500
+    x["y"][290] = -5
+    got, f, _ = check_against_oracle(wl, x, expect_status=B.FLCE_ERR_TARGET_RANGE)
+    assert f["out_of_range"] and got["n_valid"] == 298
+
+
+def test_results_are_bit_identical_between_runs():
+    wl = custom("determinism", 1024, 256, 5000, "bf16", 61, targets="zipf", ignore_frac=0.05)
+    x = I.make_inputs(wl)
+    a = run_workload(wl, x)
+    b = run_workload(wl, x)
+    for k in ("lse", "dH", "dW"):
+        assert np.array_equal(a[k], b[k]), k
+    assert a["loss"] == b["loss"]
+
+
+def test_gpt2_small_workload():
+    wl = I.WORKLOADS["gpt2_small"]
+    check_against_oracle(wl, I.make_inputs(wl))
