@@ -1,0 +1,150 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused projection + cross-entropy path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama3_8b]
+
+A step is one flce_forward + one flce_backward (every kernel of the path) over one
+batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON
+line: whole-job tokens/s, the roofline figures of the dominant kernel class (timed
+live with HIP events on the stream the kernels run on) and the CPU oracle timed on
+a bounded row sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2516.6      # MI355X dense bf16: 256 CU x 4096 flop/clk x 2.4 GHz
+F32_MFMA_PEAK_TFLOPS = 157.3
+
+
+def cpu_baseline(wl, x, rows):
+    """The oracle as it stands, on the first `rows` rows of the workload (all of W)."""
+    import numpy as np
+    from oracle import flce_oracle as O
+    from paper_2511_17599_amd import inputs as I
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    H = I.to_f64(x["H"][:rows])
+    W = I.to_f64(x["W"])
+    y = x["y"][:rows]
+    t0 = time.perf_counter()
+    f = O.forward(H, W, y, wl.ignore_index, wl.reduction)
+    b = O.backward(H, W, y, wl.ignore_index, wl.reduction)
+    dt = time.perf_counter() - t0
+    assert np.isfinite(f["loss"]) and np.isfinite(b["dW"]).all()
+    return {"value": rows / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"fp64 forward+backward of the first {rows} of {wl.N} rows against all {wl.V} vocabulary rows, "
+                      f"{dt:.1f} s wall"}, f
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="llama3_8b")
+    ap.add_argument("--oracle-rows", type=int, default=None, help="rows of the CPU baseline sample (0 = skip)")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with events")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures the one-GPU kernel path only; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2511_17599_amd import binding as B
+    from paper_2511_17599_amd import inputs as I
+    from paper_2511_17599_amd.runner import session_for
+
+    wl = I.WORKLOADS[args.workload]
+    torch.cuda.set_device(0)
+    x = I.make_inputs(wl)
+    torch.cuda.reset_peak_memory_stats()
+    s = session_for(wl, x)
+
+    def step():
+        st = s.forward()
+        assert st == B.FLCE_OK, B.flce_status_string(st)
+        st = s.backward()
+        assert st == B.FLCE_OK, B.flce_status_string(st)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    if not args.no_profile:
+        B.flce_profile_enable(1)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof_ms, prof_n = {}, {}
+    if not args.no_profile:
+        _, prof_ms, prof_n = B.flce_profile_collect()
+        B.flce_profile_enable(0)
+    st, n_valid = s.device_status()
+    assert st == B.FLCE_OK
+    loss = float(s.loss.item())
+
+    ms_per_step = dt / args.steps * 1e3
+    flops = 8.0 * wl.N * wl.d * wl.V
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+    peak = BF16_MFMA_PEAK_TFLOPS if wl.dtype == "bf16" else F32_MFMA_PEAK_TFLOPS
+
+    # roofline of the dominant kernel class (largest share of the step)
+    class_flops = {"fwd_tiles": 2.0, "recompute": 2.0, "contract_dW": 2.0, "contract_dH": 2.0}
+    kernels = {}
+    for k, c in class_flops.items():
+        if prof_n.get(k):
+            ms_step = prof_ms[k] / args.steps
+            kernels[k] = {"ms_per_step": ms_step, "launches_per_step": prof_n[k] / args.steps,
+                          "tflops": c * wl.N * wl.d * wl.V / (ms_step * 1e-3) / 1e12}
+    for k in ("fwd_epilogue", "bwd_prep"):
+        if prof_n.get(k):
+            kernels[k] = {"ms_per_step": prof_ms[k] / args.steps, "launches_per_step": prof_n[k] / args.steps}
+    roofline = None
+    if kernels:
+        dom = max(class_flops, key=lambda k: kernels.get(k, {}).get("ms_per_step", 0.0))
+        a = kernels[dom]["tflops"]
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": a, "peak": peak, "unit": "TFLOP/s", "frac": a / peak,
+                    "traffic": None,
+                    "flops_per_launch": class_flops[dom] * wl.N * wl.d * wl.V / kernels[dom]["launches_per_step"],
+                    "avg_launch_ms": kernels[dom]["ms_per_step"] / kernels[dom]["launches_per_step"]}
+
+    rows = args.oracle_rows
+    if rows is None:
+        rows = max(16, min(wl.N, int(4.0e12 / (6.0 * wl.d * wl.V))))     # ~10-20 s of fp64 work
+    base = None
+    if rows > 0:
+        base, f = cpu_baseline(wl, x, min(rows, wl.N))
+        lse_gpu = s.lse[:len(f["lse"])].float().cpu().numpy()
+        base["max_abs_lse_diff_vs_gpu"] = float(np.abs(lse_gpu - f["lse"]).max())
+
+    out = {
+        "metric": "fused linear-CE fwd+bwd tokens/sec", "value": wl.N / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "N": wl.N, "d": wl.d, "V": wl.V, "reduction": wl.reduction,
+                   "targets": wl.targets, "ignore_frac": wl.ignore_frac, "seed": wl.seed},
+        "tflops_8NdV": tflops, "frac_of_mfma_peak": tflops / peak, "loss": loss, "n_valid": n_valid,
+        "memory": {"peak_allocated_bytes": int(torch.cuda.max_memory_allocated()),
+                   "path_tensor_bytes": int(s.tensor_bytes()), "workspace_bytes": int(s.ws.numel()),
+                   "naive_fp32_logits_bytes": int(wl.naive_logits_bytes),
+                   "peak_over_naive_logits": torch.cuda.max_memory_allocated() / wl.naive_logits_bytes},
+        "roofline": roofline, "kernels": kernels, "cpu_baseline": base,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -116,6 +116,30 @@ flce_status flce_backward(const void* H, const void* W, const int64_t* targets, 
  */
 flce_status flce_last_device_status(const void* workspace, void* hip_stream, int64_t* n_valid_out);
 
+/*
+ * Measurement aid (not part of the computation; the paper's evaluation, Section 4,
+ * reports end-to-end latency only).  While enabled, every kernel launch of
+ * flce_forward / flce_backward is bracketed by a pair of HIP events recorded on the
+ * caller's stream, grouped into the classes below.  Process-wide, off by default,
+ * not meant to be toggled while another thread is inside the library.
+ *   flce_profile_enable(on) : on != 0 starts a fresh recording, 0 stops and discards.
+ *   flce_profile_collect    : waits for the recorded events, adds the elapsed
+ *                             milliseconds and launch counts per class into the two
+ *                             host arrays of FLCE_PROF_CLASSES entries (either may be
+ *                             NULL), then clears the recording (profiling stays on).
+ */
+enum {
+  FLCE_PROF_FWD_TILES = 0,   /* forward logit tiles + online softmax */
+  FLCE_PROF_FWD_EPILOGUE = 1,/* window merge, per-row loss, scalar reduction */
+  FLCE_PROF_BWD_PREP = 2,    /* target scan and K-contiguous operand copies */
+  FLCE_PROF_RECOMPUTE = 3,   /* backward logit recompute + G */
+  FLCE_PROF_CONTRACT_DW = 4, /* dW = G^T.H */
+  FLCE_PROF_CONTRACT_DH = 5, /* dH = G.W */
+  FLCE_PROF_CLASSES = 6
+};
+flce_status flce_profile_enable(int on);
+flce_status flce_profile_collect(double* ms_by_class, int64_t* launches_by_class);
+
 #ifdef __cplusplus
 }
 #endif

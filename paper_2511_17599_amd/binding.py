@@ -19,7 +19,8 @@ FLCE_DTYPE_BF16, FLCE_DTYPE_F32 = 0, 1
 FLCE_REDUCE_MEAN, FLCE_REDUCE_SUM = 0, 1
 
 EXPORTS = ("flce_version", "flce_status_string", "flce_workspace_bytes", "flce_forward", "flce_backward",
-           "flce_last_device_status")
+           "flce_last_device_status", "flce_profile_enable", "flce_profile_collect")
+PROF_CLASSES = ("fwd_tiles", "fwd_epilogue", "bwd_prep", "recompute", "contract_dW", "contract_dH")
 
 _lib = None
 
@@ -47,6 +48,10 @@ def lib():
                                     c.c_size_t, c.c_void_p]
         L.flce_last_device_status.restype = c.c_int
         L.flce_last_device_status.argtypes = [c.c_void_p, c.c_void_p, c.POINTER(c.c_int64)]
+        L.flce_profile_enable.restype = c.c_int
+        L.flce_profile_enable.argtypes = [c.c_int]
+        L.flce_profile_collect.restype = c.c_int
+        L.flce_profile_collect.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64)]
         _lib = L
     return _lib
 
@@ -97,3 +102,16 @@ def flce_last_device_status(workspace, hip_stream=None):
     nv = ctypes.c_int64(0)
     st = lib().flce_last_device_status(_ptr(workspace), _stream(hip_stream), ctypes.byref(nv))
     return st, nv.value
+
+
+def flce_profile_enable(on):
+    return lib().flce_profile_enable(int(bool(on)))
+
+
+def flce_profile_collect():
+    """Returns (status, {class: milliseconds}, {class: launches}) and clears the recording."""
+    n = len(PROF_CLASSES)
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    st = lib().flce_profile_collect(ms, cnt)
+    return st, dict(zip(PROF_CLASSES, list(ms))), dict(zip(PROF_CLASSES, list(cnt)))

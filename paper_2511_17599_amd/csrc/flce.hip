@@ -7,6 +7,7 @@
 
 #include <cstdlib>
 #include <mutex>
+#include <vector>
 
 #include "kernels.h"
 
@@ -83,6 +84,37 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   return true;
 }
 
+// Optional per-launch event timing (flce_profile_*).
+struct ProfRec { int cls; hipEvent_t a, b; };
+struct Prof {
+  std::mutex mu;
+  bool on = false;
+  std::vector<hipEvent_t> pool;
+  std::vector<ProfRec> recs;
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+};
+Prof g_prof;
+
+struct ProfScope {
+  hipStream_t st;
+  hipEvent_t b = nullptr;
+  ProfScope(int cls, hipStream_t s) : st(s) {
+    if (!g_prof.on) return;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    hipEvent_t a = g_prof.get();
+    b = g_prof.get();
+    if (!a || !b) { b = nullptr; return; }
+    (void)hipEventRecord(a, st);
+    g_prof.recs.push_back(ProfRec{cls, a, b});
+  }
+  ~ProfScope() { if (b) (void)hipEventRecord(b, st); }
+};
+
 template <typename K>
 hipError_t allow_big_lds(K kernel) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -109,12 +141,18 @@ flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t
   int* blk_cnt = reinterpret_cast<int*>(ws + p.off_blk_cnt);
   int* blk_oor = reinterpret_cast<int*>(ws + p.off_blk_oor);
   const int grid = p.n_rb * p.n_win;
-  fwd_tiles_kernel<T><<<grid, THREADS, LDS_BYTES, st>>>(static_cast<const T*>(H), static_cast<const T*>(W), y,
-                                                        (int)p.N, (int)p.d, (int)p.V, ignore_index, p.n_rb, p.n_win,
-                                                        p.n_vt, part);
-  merge_rows_kernel<<<p.n_rb, 256, 0, st>>>(part, p.n_win, p.npad, y, (int)p.N, (int)p.V, ignore_index, lse_out,
-                                            blk_loss, blk_cnt, blk_oor);
-  finalize_loss_kernel<<<1, 256, 0, st>>>(blk_loss, blk_cnt, blk_oor, p.n_rb, mean, hdr, loss_out);
+  {
+    ProfScope ps(FLCE_PROF_FWD_TILES, st);
+    fwd_tiles_kernel<T><<<grid, THREADS, LDS_BYTES, st>>>(static_cast<const T*>(H), static_cast<const T*>(W), y,
+                                                          (int)p.N, (int)p.d, (int)p.V, ignore_index, p.n_rb,
+                                                          p.n_win, p.n_vt, part);
+  }
+  {
+    ProfScope ps(FLCE_PROF_FWD_EPILOGUE, st);
+    merge_rows_kernel<<<p.n_rb, 256, 0, st>>>(part, p.n_win, p.npad, y, (int)p.N, (int)p.V, ignore_index, lse_out,
+                                              blk_loss, blk_cnt, blk_oor);
+    finalize_loss_kernel<<<1, 256, 0, st>>>(blk_loss, blk_cnt, blk_oor, p.n_rb, mean, hdr, loss_out);
+  }
   return hipGetLastError() == hipSuccess ? FLCE_OK : FLCE_ERR_HIP;
 }
 
@@ -134,28 +172,38 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
   const int64_t vc_pad = (int64_t)p.vc_tiles * TILE, nc_pad = (int64_t)p.nc_tiles * TILE;
   const int n_mt = (int)ceil_div(d, TILE);
 
-  scan_targets_kernel<<<1, 1024, 0, st>>>(y, N, V, ignore_index, hdr);
-  // H^T [d][npad]: K-contiguous operand of the dW contraction
-  transpose_pad_kernel<U><<<dim3((unsigned)ceil_div(p.npad, 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
-      static_cast<const U*>(H), d, N, 0, d, reinterpret_cast<U*>(HT), p.npad, (int)p.npad);
+  {
+    ProfScope ps(FLCE_PROF_BWD_PREP, st);
+    scan_targets_kernel<<<1, 1024, 0, st>>>(y, N, V, ignore_index, hdr);
+    // H^T [d][npad]: K-contiguous operand of the dW contraction
+    transpose_pad_kernel<U><<<dim3((unsigned)ceil_div(p.npad, 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
+        static_cast<const U*>(H), d, N, 0, d, reinterpret_cast<U*>(HT), p.npad, (int)p.npad);
+  }
 
   for (int vc = 0; vc < p.n_vch; ++vc) {
     const int vt0 = (int)((int64_t)vc * p.n_vt / p.n_vch), vt1 = (int)((int64_t)(vc + 1) * p.n_vt / p.n_vch);
     const int n_vt = vt1 - vt0;
-    // W^T chunk [d][vc_pad]: K-contiguous operand of the dH contraction
-    transpose_pad_kernel<U><<<dim3((unsigned)(n_vt * TILE / 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
-        static_cast<const U*>(W), d, V, vt0 * TILE, d, reinterpret_cast<U*>(WT), vc_pad, n_vt * TILE);
+    {
+      // W^T chunk [d][vc_pad]: K-contiguous operand of the dH contraction
+      ProfScope ps(FLCE_PROF_BWD_PREP, st);
+      transpose_pad_kernel<U><<<dim3((unsigned)(n_vt * TILE / 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
+          static_cast<const U*>(W), d, V, vt0 * TILE, d, reinterpret_cast<U*>(WT), vc_pad, n_vt * TILE);
+    }
     for (int nc = 0; nc < p.n_nch; ++nc) {
       const int nt0 = (int)((int64_t)nc * p.n_rb / p.n_nch), nt1 = (int)((int64_t)(nc + 1) * p.n_rb / p.n_nch);
       const int n_nt = nt1 - nt0;
-      recompute_kernel<T><<<n_nt * n_vt, THREADS, LDS_BYTES, st>>>(
-          static_cast<const T*>(H), static_cast<const T*>(W), y, lse, N, d, V, ignore_index, nt0, n_nt, vt0, n_vt, G,
-          vc_pad, GT, nc_pad);
+      {
+        ProfScope ps(FLCE_PROF_RECOMPUTE, st);
+        recompute_kernel<T><<<n_nt * n_vt, THREADS, LDS_BYTES, st>>>(
+            static_cast<const T*>(H), static_cast<const T*>(W), y, lse, N, d, V, ignore_index, nt0, n_nt, vt0, n_vt,
+            G, vc_pad, GT, nc_pad);
+      }
       // dW[vocab chunk] += GT . H^T[:, token chunk]^T   (contraction over the token chunk)
       {
         int flags = 0;
         if (nc > 0) flags |= READ_ACC;
         flags |= (nc + 1 < p.n_nch) ? WRITE_ACC : WRITE_OUT;
+        ProfScope ps(FLCE_PROF_CONTRACT_DW, st);
         contract_kernel<T><<<n_vt * n_mt, THREADS, LDS_BYTES, st>>>(
             HT + (int64_t)nt0 * TILE, p.npad, d, GT, nc_pad, n_vt * TILE, n_nt * TILE, n_mt, n_vt, dWacc,
             vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags, hdr, grad_loss, mean);
@@ -165,6 +213,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
         int flags = 0;
         if (vc > 0) flags |= READ_ACC;
         flags |= (vc + 1 < p.n_vch) ? WRITE_ACC : WRITE_OUT;
+        ProfScope ps(FLCE_PROF_CONTRACT_DH, st);
         contract_kernel<T><<<n_nt * n_mt, THREADS, LDS_BYTES, st>>>(
             WT, vc_pad, d, G, vc_pad, n_nt * TILE, n_vt * TILE, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH),
             nt0 * TILE, N, flags, hdr, grad_loss, mean);
@@ -252,6 +301,31 @@ flce_status flce_last_device_status(const void* workspace, void* hip_stream, int
   if (hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return FLCE_ERR_HIP;
   if (n_valid_out) *n_valid_out = h.n_valid;
   return h.status == 0 ? FLCE_OK : FLCE_ERR_TARGET_RANGE;
+}
+
+flce_status flce_profile_enable(int on) {
+  std::lock_guard<std::mutex> lk(flce::g_prof.mu);
+  for (auto& r : flce::g_prof.recs) { flce::g_prof.pool.push_back(r.a); flce::g_prof.pool.push_back(r.b); }
+  flce::g_prof.recs.clear();
+  flce::g_prof.on = on != 0;
+  return FLCE_OK;
+}
+
+flce_status flce_profile_collect(double* ms_by_class, int64_t* launches_by_class) {
+  std::lock_guard<std::mutex> lk(flce::g_prof.mu);
+  flce_status rc = FLCE_OK;
+  for (auto& r : flce::g_prof.recs) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) rc = FLCE_ERR_HIP;
+    if (r.cls >= 0 && r.cls < FLCE_PROF_CLASSES) {
+      if (ms_by_class) ms_by_class[r.cls] += (double)ms;
+      if (launches_by_class) launches_by_class[r.cls] += 1;
+    }
+    flce::g_prof.pool.push_back(r.a);
+    flce::g_prof.pool.push_back(r.b);
+  }
+  flce::g_prof.recs.clear();
+  return rc;
 }
 
 }  // extern "C"
