@@ -116,25 +116,33 @@ struct ProfScope {
 };
 
 template <typename K>
-hipError_t allow_big_lds(K kernel) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             LDS_BYTES);
+hipError_t allow_big_lds(K kernel, int bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
-template <typename T>
+template <typename T, typename L>
 hipError_t prepare_kernels() {
   hipError_t e;
-  if ((e = allow_big_lds(fwd_tiles_kernel<T>)) != hipSuccess) return e;
-  if ((e = allow_big_lds(recompute_kernel<T>)) != hipSuccess) return e;
-  if ((e = allow_big_lds(contract_kernel<T>)) != hipSuccess) return e;
+  if ((e = allow_big_lds(fwd_tiles_kernel<T, L>, L::LDS)) != hipSuccess) return e;
+  if ((e = allow_big_lds(recompute_kernel<T, L>, L::LDS)) != hipSuccess) return e;
+  if ((e = allow_big_lds(contract_kernel<T, L>, L::LDS)) != hipSuccess) return e;
   return hipSuccess;
 }
 
+// The tuned bf16 loop needs K extents that are multiples of 32 elements and row
+// pitches below 2^23 bytes; FLCE_GENERIC=1 forces the generic loop everywhere.
+bool fast_loop_ok(const Plan& p) {
+  if (p.esize != 2 || env_int("FLCE_GENERIC", 0, 0, 1)) return false;
+  const int64_t lim = (int64_t)1 << 23;
+  return p.d % 32 == 0 && p.d * 2 < lim && p.npad * 2 < lim && (int64_t)p.vc_tiles * TILE * 2 < lim &&
+         (int64_t)p.nc_tiles * TILE * 2 < lim;
+}
+
 // The attribute is per device; set it on every call's current device (a cheap host-side call).
-template <typename T>
+template <typename T, typename L>
 flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t* y, int64_t ignore_index,
                       int mean, float* loss_out, float* lse_out, char* ws, hipStream_t st) {
-  if (prepare_kernels<T>() != hipSuccess) return FLCE_ERR_HIP;
+  if (prepare_kernels<T, L>() != hipSuccess) return FLCE_ERR_HIP;
   Header* hdr = reinterpret_cast<Header*>(ws);
   float* part = reinterpret_cast<float*>(ws + p.off_part);
   float* blk_loss = reinterpret_cast<float*>(ws + p.off_blk_loss);
@@ -143,7 +151,7 @@ flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t
   const int grid = p.n_rb * p.n_win;
   {
     ProfScope ps(FLCE_PROF_FWD_TILES, st);
-    fwd_tiles_kernel<T><<<grid, THREADS, LDS_BYTES, st>>>(static_cast<const T*>(H), static_cast<const T*>(W), y,
+    fwd_tiles_kernel<T, L><<<grid, L::THREADS, L::LDS, st>>>(static_cast<const T*>(H), static_cast<const T*>(W), y,
                                                           (int)p.N, (int)p.d, (int)p.V, ignore_index, p.n_rb,
                                                           p.n_win, p.n_vt, part);
   }
@@ -156,11 +164,11 @@ flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t
   return hipGetLastError() == hipSuccess ? FLCE_OK : FLCE_ERR_HIP;
 }
 
-template <typename T, typename U>
+template <typename T, typename U, typename L>
 flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_t* y, const float* lse,
                        int64_t ignore_index, int mean, float grad_loss, void* dH, void* dW, char* ws,
                        hipStream_t st) {
-  if (prepare_kernels<T>() != hipSuccess) return FLCE_ERR_HIP;
+  if (prepare_kernels<T, L>() != hipSuccess) return FLCE_ERR_HIP;
   const int N = (int)p.N, d = (int)p.d, V = (int)p.V;
   Header* hdr = reinterpret_cast<Header*>(ws);
   T* HT = reinterpret_cast<T*>(ws + p.off_HT);
@@ -194,7 +202,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
       const int n_nt = nt1 - nt0;
       {
         ProfScope ps(FLCE_PROF_RECOMPUTE, st);
-        recompute_kernel<T><<<n_nt * n_vt, THREADS, LDS_BYTES, st>>>(
+        recompute_kernel<T, L><<<n_nt * n_vt, L::THREADS, L::LDS, st>>>(
             static_cast<const T*>(H), static_cast<const T*>(W), y, lse, N, d, V, ignore_index, nt0, n_nt, vt0, n_vt,
             G, vc_pad, GT, nc_pad);
       }
@@ -204,7 +212,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
         if (nc > 0) flags |= READ_ACC;
         flags |= (nc + 1 < p.n_nch) ? WRITE_ACC : WRITE_OUT;
         ProfScope ps(FLCE_PROF_CONTRACT_DW, st);
-        contract_kernel<T><<<n_vt * n_mt, THREADS, LDS_BYTES, st>>>(
+        contract_kernel<T, L><<<n_vt * n_mt, L::THREADS, L::LDS, st>>>(
             HT + (int64_t)nt0 * TILE, p.npad, d, GT, nc_pad, n_vt * TILE, n_nt * TILE, n_mt, n_vt, dWacc,
             vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags, hdr, grad_loss, mean);
       }
@@ -214,7 +222,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
         if (vc > 0) flags |= READ_ACC;
         flags |= (vc + 1 < p.n_vch) ? WRITE_ACC : WRITE_OUT;
         ProfScope ps(FLCE_PROF_CONTRACT_DH, st);
-        contract_kernel<T><<<n_nt * n_mt, THREADS, LDS_BYTES, st>>>(
+        contract_kernel<T, L><<<n_nt * n_mt, L::THREADS, L::LDS, st>>>(
             WT, vc_pad, d, G, vc_pad, n_nt * TILE, n_vt * TILE, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH),
             nt0 * TILE, N, flags, hdr, grad_loss, mean);
       }
@@ -265,9 +273,15 @@ flce_status flce_forward(const void* H, const void* W, const int64_t* targets, i
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int mean = reduction == FLCE_REDUCE_MEAN;
   char* ws = static_cast<char*>(workspace);
-  if (dt == FLCE_DTYPE_BF16)
-    return flce::forward_t<flce::bf16_t>(p, H, W, targets, ignore_index, mean, loss_out, lse_out, ws, st);
-  return flce::forward_t<float>(p, H, W, targets, ignore_index, mean, loss_out, lse_out, ws, st);
+  if (dt == FLCE_DTYPE_BF16) {
+    if (flce::fast_loop_ok(p))
+      return flce::forward_t<flce::bf16_t, flce::FastLoop>(p, H, W, targets, ignore_index, mean, loss_out, lse_out,
+                                                           ws, st);
+    return flce::forward_t<flce::bf16_t, flce::GenericLoop<flce::bf16_t>>(p, H, W, targets, ignore_index, mean,
+                                                                          loss_out, lse_out, ws, st);
+  }
+  return flce::forward_t<float, flce::GenericLoop<float>>(p, H, W, targets, ignore_index, mean, loss_out, lse_out, ws,
+                                                          st);
 }
 
 flce_status flce_backward(const void* H, const void* W, const int64_t* targets, const float* lse, int64_t N,
@@ -286,11 +300,15 @@ flce_status flce_backward(const void* H, const void* W, const int64_t* targets, 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int mean = reduction == FLCE_REDUCE_MEAN;
   char* ws = static_cast<char*>(workspace);
-  if (dt == FLCE_DTYPE_BF16)
-    return flce::backward_t<flce::bf16_t, uint16_t>(p, H, W, targets, lse, ignore_index, mean, grad_loss, dH_out,
-                                                    dW_out, ws, st);
-  return flce::backward_t<float, uint32_t>(p, H, W, targets, lse, ignore_index, mean, grad_loss, dH_out, dW_out, ws,
-                                           st);
+  if (dt == FLCE_DTYPE_BF16) {
+    if (flce::fast_loop_ok(p))
+      return flce::backward_t<flce::bf16_t, uint16_t, flce::FastLoop>(p, H, W, targets, lse, ignore_index, mean,
+                                                                      grad_loss, dH_out, dW_out, ws, st);
+    return flce::backward_t<flce::bf16_t, uint16_t, flce::GenericLoop<flce::bf16_t>>(
+        p, H, W, targets, lse, ignore_index, mean, grad_loss, dH_out, dW_out, ws, st);
+  }
+  return flce::backward_t<float, uint32_t, flce::GenericLoop<float>>(p, H, W, targets, lse, ignore_index, mean,
+                                                                     grad_loss, dH_out, dW_out, ws, st);
 }
 
 flce_status flce_last_device_status(const void* workspace, void* hip_stream, int64_t* n_valid_out) {

@@ -13,9 +13,46 @@
 //             contract_kernel (Eq. 4 and Eq. 5 as output-stationary MFMA
 //             contractions with a fixed chunk order; Gamma applied at the flush)
 #pragma once
+#include "mainloop_fast.h"
 #include "tile_mma.h"
 
 namespace flce {
+
+// Main-loop policies.  A kernel is written once against this interface:
+//   THREADS, WM x WN (32x32 accumulator blocks per wavefront), LDS (dynamic LDS bytes),
+//   tile_m(i, r) / tile_n(j): position of acc[i][j][r] inside the 256 x 256 tile,
+//   slot(): which of the 4 lanes that share an N column this lane is,
+//   run(): acc = A_tile . B_tile^T, ending with a barrier after the last LDS read.
+template <typename T>
+struct GenericLoop {      // any dtype, any K that is a multiple of 16 bytes; 8 wavefronts 2 x 4
+  static constexpr int THREADS = flce::THREADS, WM = flce::WM, WN = flce::WN, LDS = LDS_BYTES;
+  static __device__ __forceinline__ int tile_m(int i, int r) { return flce::tile_m(i, r); }
+  static __device__ __forceinline__ int tile_n(int j) { return flce::tile_n(j); }
+  static __device__ __forceinline__ int slot() {
+    return ((threadIdx.x >> 6) >> 2) * 2 + ((threadIdx.x & 63) >> 5);
+  }
+  static __device__ __forceinline__ void run(const void* A, int64_t lda_bytes, int a_row0, int a_rows, const void* B,
+                                             int64_t ldb_bytes, int b_row0, int b_rows, int k_bytes, char* lds,
+                                             f32x16 (&acc)[WM][WN]) {
+    const TileSrc As{static_cast<const char*>(A), lda_bytes, a_row0, a_rows};
+    const TileSrc Bs{static_cast<const char*>(B), ldb_bytes, b_row0, b_rows};
+    tile_mainloop<T>(As, Bs, k_bytes, lds, acc);
+  }
+};
+
+struct FastLoop {         // bf16, K a multiple of 32 elements; 4 wavefronts 2 x 2, global -> LDS DMA
+  static constexpr int THREADS = fast::THREADS, WM = fast::WM, WN = fast::WN, LDS = fast::LDS_BYTES;
+  static __device__ __forceinline__ int tile_m(int i, int r) { return fast::tile_m(i, r); }
+  static __device__ __forceinline__ int tile_n(int j) { return fast::tile_n(j); }
+  static __device__ __forceinline__ int slot() { return fast::slot_of_lane(); }
+  static __device__ __forceinline__ void run(const void* A, int64_t lda_bytes, int a_row0, int a_rows, const void* B,
+                                             int64_t ldb_bytes, int b_row0, int b_rows, int k_bytes, char* lds,
+                                             f32x16 (&acc)[WM][WN]) {
+    const fast::Src As{static_cast<const char*>(A), lda_bytes, a_row0, a_rows};
+    const fast::Src Bs{static_cast<const char*>(B), ldb_bytes, b_row0, b_rows};
+    fast::mainloop(As, Bs, k_bytes, lds, acc);
+  }
+};
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float NEG_INF = -__builtin_inff();
@@ -58,8 +95,8 @@ __device__ __forceinline__ void merge_fixed(const float (&m)[S], const float (&a
 // (m, a, z_target) in registers across the vocabulary tiles of its window.
 // part = [3][n_win][n_rb * 256] floats: m, a, z_target per (window, row).
 // ------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(THREADS) void fwd_tiles_kernel(
+template <typename T, typename L>
+__global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
     const T* __restrict__ H, const T* __restrict__ W, const int64_t* __restrict__ y,
     int N, int d, int V, int64_t ignore_index, int n_rb, int n_win, int n_vt, float* __restrict__ part) {
   extern __shared__ __align__(16) char lds[];
@@ -71,45 +108,43 @@ __global__ __launch_bounds__(THREADS) void fwd_tiles_kernel(
   const int n0 = rb * TILE;
   const int64_t ld_bytes = (int64_t)d * sizeof(T);
 
-  int tgt[WN];
-  float m[WN], a[WN], zt[WN];
+  int tgt[L::WN];
+  float m[L::WN], a[L::WN], zt[L::WN];
 #pragma unroll
-  for (int j = 0; j < WN; ++j) {
-    const int n = n0 + tile_n(j);
+  for (int j = 0; j < L::WN; ++j) {
+    const int n = n0 + L::tile_n(j);
     bool oor;
     tgt[j] = (n < N) ? classify_target(y[n], ignore_index, V, oor) : -1;
     m[j] = NEG_INF; a[j] = 0.f; zt[j] = 0.f;
   }
 
-  const TileSrc Bsrc{reinterpret_cast<const char*>(H), ld_bytes, n0, N};
-  f32x16 acc[WM][WN];
+  f32x16 acc[L::WM][L::WN];
   for (int vt = vt_begin; vt < vt_end; ++vt) {
     const int v0 = vt * TILE;
-    const TileSrc Asrc{reinterpret_cast<const char*>(W), ld_bytes, v0, V};
-    tile_mainloop<T>(Asrc, Bsrc, (int)ld_bytes, lds, acc);
+    L::run(W, ld_bytes, v0, V, H, ld_bytes, n0, N, (int)ld_bytes, lds, acc);
 
     if (v0 + TILE > V) {       // ragged last vocabulary tile: padded logits are -inf
 #pragma unroll
-      for (int i = 0; i < WM; ++i)
+      for (int i = 0; i < L::WM; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-          if (v0 + tile_m(i, r) >= V) {
+          if (v0 + L::tile_m(i, r) >= V) {
 #pragma unroll
-            for (int j = 0; j < WN; ++j) acc[i][j][r] = NEG_INF;
+            for (int j = 0; j < L::WN; ++j) acc[i][j][r] = NEG_INF;
           }
     }
 #pragma unroll
-    for (int j = 0; j < WN; ++j) {
+    for (int j = 0; j < L::WN; ++j) {
       float tmax = NEG_INF;
 #pragma unroll
-      for (int i = 0; i < WM; ++i)
+      for (int i = 0; i < L::WM; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, acc[i][j][r]);
       const float mn = fmaxf(m[j], tmax);
       const float ms = (mn == NEG_INF) ? 0.f : mn;     // all-padded slice: keep exp arguments finite
       float sum = 0.f;
 #pragma unroll
-      for (int i = 0; i < WM; ++i)
+      for (int i = 0; i < L::WM; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) sum += fast_exp2((acc[i][j][r] - ms) * LOG2E);
       a[j] = a[j] * fast_exp2((m[j] - ms) * LOG2E) + sum;
@@ -119,10 +154,10 @@ __global__ __launch_bounds__(THREADS) void fwd_tiles_kernel(
       const bool mine = (unsigned)rel < (unsigned)TILE && tgt[j] >= 0;
       if (__ballot(mine) != 0ull) {
 #pragma unroll
-        for (int i = 0; i < WM; ++i)
+        for (int i = 0; i < L::WM; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r)
-            if (mine && tile_m(i, r) == rel) zt[j] = acc[i][j][r];
+            if (mine && L::tile_m(i, r) == rel) zt[j] = acc[i][j][r];
       }
     }
   }
@@ -133,11 +168,10 @@ __global__ __launch_bounds__(THREADS) void fwd_tiles_kernel(
   float* sa = sm + 4 * TILE;
   float* sz = sa + 4 * TILE;
   {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int slot = (wave >> 2) * 2 + (lane >> 5);
+    const int slot = L::slot();
 #pragma unroll
-    for (int j = 0; j < WN; ++j) {
-      const int tok = tile_n(j);
+    for (int j = 0; j < L::WN; ++j) {
+      const int tok = L::tile_n(j);
       sm[slot * TILE + tok] = m[j];
       sa[slot * TILE + tok] = a[j];
       sz[slot * TILE + tok] = zt[j];
@@ -321,8 +355,8 @@ template <> struct Pack4<bf16_t> {
 //   GT[vocab - chunk_v0][token - chunk_n0]   (ldGT elements per row)
 // Padded vocabulary columns and padded / ignored token rows are written as 0.
 // ------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(THREADS) void recompute_kernel(
+template <typename T, typename L>
+__global__ __launch_bounds__(L::THREADS) void recompute_kernel(
     const T* __restrict__ H, const T* __restrict__ W, const int64_t* __restrict__ y, const float* __restrict__ lse,
     int N, int d, int V, int64_t ignore_index, int nt0, int n_nt, int vt0, int n_vt,
     T* __restrict__ G, int64_t ldG, T* __restrict__ GT, int64_t ldGT) {
@@ -332,24 +366,22 @@ __global__ __launch_bounds__(THREADS) void recompute_kernel(
   grouped_raster(id, n_nt, n_vt, 8, p, q);
   const int n0 = (nt0 + p) * TILE, v0 = (vt0 + q) * TILE;
   const int64_t ld_bytes = (int64_t)d * sizeof(T);
-  const TileSrc Asrc{reinterpret_cast<const char*>(W), ld_bytes, v0, V};
-  const TileSrc Bsrc{reinterpret_cast<const char*>(H), ld_bytes, n0, N};
-  f32x16 acc[WM][WN];
-  tile_mainloop<T>(Asrc, Bsrc, (int)ld_bytes, lds, acc);
+  f32x16 acc[L::WM][L::WN];
+  L::run(W, ld_bytes, v0, V, H, ld_bytes, n0, N, (int)ld_bytes, lds, acc);
 
 #pragma unroll
-  for (int j = 0; j < WN; ++j) {
-    const int nl = p * TILE + tile_n(j);       // row inside the staging tile
-    const int n = n0 + tile_n(j);
+  for (int j = 0; j < L::WN; ++j) {
+    const int nl = p * TILE + L::tile_n(j);       // row inside the staging tile
+    const int n = n0 + L::tile_n(j);
     bool oor;
     const int tgt = (n < N) ? classify_target(y[n], ignore_index, V, oor) : -1;
     const bool counted = tgt >= 0;
     const float l = (n < N) ? lse[n] : 0.f;
 #pragma unroll
-    for (int i = 0; i < WM; ++i)
+    for (int i = 0; i < L::WM; ++i)
 #pragma unroll
       for (int rq = 0; rq < 4; ++rq) {
-        const int mloc = tile_m(i, rq * 4);    // first of 4 consecutive vocabulary positions
+        const int mloc = L::tile_m(i, rq * 4);    // first of 4 consecutive vocabulary positions
         float g[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -375,8 +407,8 @@ __global__ __launch_bounds__(THREADS) void recompute_kernel(
 // ------------------------------------------------------------------------------------
 enum : int { READ_ACC = 1, WRITE_ACC = 2, WRITE_OUT = 4 };
 
-template <typename T>
-__global__ __launch_bounds__(THREADS) void contract_kernel(
+template <typename T, typename L>
+__global__ __launch_bounds__(L::THREADS) void contract_kernel(
     const T* __restrict__ A, int64_t lda, int d, const T* __restrict__ B, int64_t ldb, int b_rows, int k_elems,
     int n_mt, int n_nt, float* __restrict__ accbuf, int acc_row0, T* __restrict__ out, int out_row0, int out_rows,
     int flags, const Header* __restrict__ hdr, float grad_loss, int mean) {
@@ -384,10 +416,9 @@ __global__ __launch_bounds__(THREADS) void contract_kernel(
   const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
   int p, q;                                    // output-row tile, hidden tile
   grouped_raster(id, n_nt, n_mt, 8, p, q);
-  const TileSrc Asrc{reinterpret_cast<const char*>(A), lda * (int64_t)sizeof(T), q * TILE, d};
-  const TileSrc Bsrc{reinterpret_cast<const char*>(B), ldb * (int64_t)sizeof(T), p * TILE, b_rows};
-  f32x16 acc[WM][WN];
-  tile_mainloop<T>(Asrc, Bsrc, k_elems * (int)sizeof(T), lds, acc);
+  f32x16 acc[L::WM][L::WN];
+  L::run(A, lda * (int64_t)sizeof(T), q * TILE, d, B, ldb * (int64_t)sizeof(T), p * TILE, b_rows,
+         k_elems * (int)sizeof(T), lds, acc);
 
   float scale = grad_loss;
   if (mean) {
@@ -395,14 +426,14 @@ __global__ __launch_bounds__(THREADS) void contract_kernel(
     scale = nv > 0 ? grad_loss / (float)nv : 0.f;
   }
 #pragma unroll
-  for (int j = 0; j < WN; ++j) {
-    const int n = out_row0 + p * TILE + tile_n(j);
+  for (int j = 0; j < L::WN; ++j) {
+    const int n = out_row0 + p * TILE + L::tile_n(j);
     if (n >= out_rows) continue;
 #pragma unroll
-    for (int i = 0; i < WM; ++i)
+    for (int i = 0; i < L::WM; ++i)
 #pragma unroll
       for (int rq = 0; rq < 4; ++rq) {
-        const int m = q * TILE + tile_m(i, rq * 4);
+        const int m = q * TILE + L::tile_m(i, rq * 4);
         if (m >= d) continue;
         f32x4 v = {acc[i][j][rq * 4], acc[i][j][rq * 4 + 1], acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]};
         float* ap = accbuf + (int64_t)(n - acc_row0) * d + m;
