@@ -40,7 +40,7 @@ struct Plan {
   // backward
   int n_vch, n_nch;        // chunks along vocabulary / tokens
   int vc_tiles, nc_tiles;  // largest chunk, in tiles
-  int64_t off_HT, off_WT, off_G, off_GT, off_dHacc, off_dWacc, bwd_bytes;
+  int64_t off_Hc, off_rowmap, off_tgt, off_lsec, off_HT, off_WT, off_G, off_GT, off_dHacc, off_dWacc, bwd_bytes;
 };
 
 bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
@@ -66,7 +66,7 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   p.fwd_bytes = o;
 
   // Backward staging: a fixed-size G tile of at most vc x nc 256-tiles.
-  const int vc_max = env_int("FLCE_VC_TILES", 32, 1, 4096);
+  const int vc_max = env_int("FLCE_VC_TILES", 64, 1, 4096);
   const int nc_max = env_int("FLCE_NC_TILES", 32, 1, 4096);
   p.n_vch = (int)ceil_div(p.n_vt, vc_max);
   p.n_nch = (int)ceil_div(p.n_rb, nc_max);
@@ -74,6 +74,10 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   p.nc_tiles = (int)ceil_div(p.n_rb, p.n_nch);
   const int64_t vc_pad = (int64_t)p.vc_tiles * TILE, nc_pad = (int64_t)p.nc_tiles * TILE;
   o = ALIGN;
+  p.off_Hc = o;     o = align_up(o + d * p.npad * p.esize, ALIGN);
+  p.off_rowmap = o; o = align_up(o + p.npad * 4, ALIGN);
+  p.off_tgt = o;    o = align_up(o + p.npad * 4, ALIGN);
+  p.off_lsec = o;   o = align_up(o + p.npad * 4, ALIGN);
   p.off_HT = o;     o = align_up(o + d * p.npad * p.esize, ALIGN);
   p.off_WT = o;     o = align_up(o + d * vc_pad * p.esize, ALIGN);
   p.off_G = o;      o = align_up(o + nc_pad * vc_pad * p.esize, ALIGN);
@@ -171,6 +175,10 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
   if (prepare_kernels<T, L>() != hipSuccess) return FLCE_ERR_HIP;
   const int N = (int)p.N, d = (int)p.d, V = (int)p.V;
   Header* hdr = reinterpret_cast<Header*>(ws);
+  T* Hc = reinterpret_cast<T*>(ws + p.off_Hc);
+  int* rowmap = reinterpret_cast<int*>(ws + p.off_rowmap);
+  int* tgt_c = reinterpret_cast<int*>(ws + p.off_tgt);
+  float* lse_c = reinterpret_cast<float*>(ws + p.off_lsec);
   T* HT = reinterpret_cast<T*>(ws + p.off_HT);
   T* WT = reinterpret_cast<T*>(ws + p.off_WT);
   T* G = reinterpret_cast<T*>(ws + p.off_G);
@@ -179,13 +187,18 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
   float* dWacc = reinterpret_cast<float*>(ws + p.off_dWacc);
   const int64_t vc_pad = (int64_t)p.vc_tiles * TILE, nc_pad = (int64_t)p.nc_tiles * TILE;
   const int n_mt = (int)ceil_div(d, TILE);
+  const int npad = (int)p.npad;
+  const int64_t row_bytes = (int64_t)d * sizeof(T);
 
   {
     ProfScope ps(FLCE_PROF_BWD_PREP, st);
-    scan_targets_kernel<<<1, 1024, 0, st>>>(y, N, V, ignore_index, hdr);
-    // H^T [d][npad]: K-contiguous operand of the dW contraction
+    compact_targets_kernel<<<1, 1024, 0, st>>>(y, N, V, ignore_index, npad, rowmap, tgt_c, hdr);
+    gather_rows_kernel<<<npad, 256, 0, st>>>(static_cast<const char*>(H), row_bytes, rowmap, lse,
+                                             reinterpret_cast<char*>(Hc), lse_c);
+    zero_uncounted_rows_kernel<<<N, 256, 0, st>>>(y, V, ignore_index, static_cast<char*>(dH), row_bytes);
+    // Hc^T [d][npad]: K-contiguous operand of the dW contraction
     transpose_pad_kernel<U><<<dim3((unsigned)ceil_div(p.npad, 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
-        static_cast<const U*>(H), d, N, 0, d, reinterpret_cast<U*>(HT), p.npad, (int)p.npad);
+        reinterpret_cast<const U*>(Hc), d, npad, 0, d, reinterpret_cast<U*>(HT), p.npad, npad);
   }
 
   for (int vc = 0; vc < p.n_vch; ++vc) {
@@ -202,29 +215,29 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
       const int n_nt = nt1 - nt0;
       {
         ProfScope ps(FLCE_PROF_RECOMPUTE, st);
-        recompute_kernel<T, L><<<n_nt * n_vt, L::THREADS, L::LDS, st>>>(
-            static_cast<const T*>(H), static_cast<const T*>(W), y, lse, N, d, V, ignore_index, nt0, n_nt, vt0, n_vt,
-            G, vc_pad, GT, nc_pad);
+        recompute_kernel<T, L><<<n_nt * n_vt, L::THREADS, L::LDS, st>>>(Hc, static_cast<const T*>(W), tgt_c, lse_c, hdr,
+                                                                        npad, d, V, nt0, n_nt, vt0, n_vt, G, vc_pad,
+                                                                        GT, nc_pad);
       }
-      // dW[vocab chunk] += GT . H^T[:, token chunk]^T   (contraction over the token chunk)
+      // dW[vocab chunk] += GT . Hc^T[:, row chunk]^T   (contraction over the compact rows of the chunk)
       {
-        int flags = 0;
+        int flags = K_COMPACT;
         if (nc > 0) flags |= READ_ACC;
         flags |= (nc + 1 < p.n_nch) ? WRITE_ACC : WRITE_OUT;
         ProfScope ps(FLCE_PROF_CONTRACT_DW, st);
         contract_kernel<T, L><<<n_vt * n_mt, L::THREADS, L::LDS, st>>>(
-            HT + (int64_t)nt0 * TILE, p.npad, d, GT, nc_pad, n_vt * TILE, n_nt * TILE, n_mt, n_vt, dWacc,
-            vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags, hdr, grad_loss, mean);
+            HT + (int64_t)nt0 * TILE, p.npad, d, GT, nc_pad, n_vt * TILE, n_nt * TILE, nt0 * TILE, n_mt, n_vt, dWacc,
+            vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags, hdr, rowmap, grad_loss, mean);
       }
-      // dH[token chunk] += G . W^T[:, vocab chunk]^T    (contraction over the vocabulary chunk)
+      // dH[row chunk] += G . W^T[:, vocab chunk]^T     (contraction over the vocabulary chunk)
       {
-        int flags = 0;
+        int flags = ROWS_COMPACT;
         if (vc > 0) flags |= READ_ACC;
         flags |= (vc + 1 < p.n_vch) ? WRITE_ACC : WRITE_OUT;
         ProfScope ps(FLCE_PROF_CONTRACT_DH, st);
         contract_kernel<T, L><<<n_nt * n_mt, L::THREADS, L::LDS, st>>>(
-            WT, vc_pad, d, G, vc_pad, n_nt * TILE, n_vt * TILE, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH),
-            nt0 * TILE, N, flags, hdr, grad_loss, mean);
+            WT, vc_pad, d, G, vc_pad, n_nt * TILE, n_vt * TILE, 0, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH),
+            nt0 * TILE, npad, flags, hdr, rowmap, grad_loss, mean);
       }
     }
   }

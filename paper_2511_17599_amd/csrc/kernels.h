@@ -5,7 +5,8 @@
 //             vocabulary window: Section 3.2.1)
 //             merge_rows_kernel + finalize_loss_kernel (the merging epilogue of
 //             Section 3.2.1, lse = m + ln a, per-row loss, fixed-order sums)
-//   backward: scan_targets_kernel (n_valid, range flag)
+//   backward: compact_targets_kernel + gather_rows_kernel (n_valid, range flag, and the
+//             rows that count packed together: ignored rows have a zero row of G)
 //             transpose_pad_kernel (K-contiguous copies of H and W for the two
 //             gradient contractions)
 //             recompute_kernel (Alg. 2: z recomputed, g = p - onehot, written once to
@@ -280,30 +281,81 @@ __global__ __launch_bounds__(256) void finalize_loss_kernel(
   }
 }
 
-// Backward's integer pass over the targets: n_valid and the range flag (exact).
-__global__ __launch_bounds__(1024) void scan_targets_kernel(const int64_t* __restrict__ y, int N, int V,
-                                                            int64_t ignore_index, Header* __restrict__ hdr) {
+// Backward's integer pass over the targets (exact): n_valid, the range flag, and the
+// compaction map.  Rows that do not count have an all-zero row of G, so the three
+// backward contractions run on the counted rows only, packed in ascending row order:
+//   rowmap[c] = original row of compact row c   (c < n_valid),  -1 for c >= n_valid
+//   tgt_c[c]  = its target id,                                   -1 for c >= n_valid
+// One block; every thread owns a contiguous range of rows, an exclusive scan of the
+// per-thread counts gives each range its first compact index.
+__global__ __launch_bounds__(1024) void compact_targets_kernel(const int64_t* __restrict__ y, int N, int V,
+                                                               int64_t ignore_index, int npad,
+                                                               int* __restrict__ rowmap, int* __restrict__ tgt_c,
+                                                               Header* __restrict__ hdr) {
   __shared__ int sc[1024];
   __shared__ int so[1024];
+  const int t = threadIdx.x;
+  const int per = (N + 1023) / 1024;
+  const int r0 = min(N, t * per), r1 = min(N, r0 + per);
   int c = 0, o = 0;
-  for (int n = threadIdx.x; n < N; n += 1024) {
+  for (int n = r0; n < r1; ++n) {
     bool oor;
     if (classify_target(y[n], ignore_index, V, oor) >= 0) ++c;
     o |= oor ? 1 : 0;
   }
-  sc[threadIdx.x] = c; so[threadIdx.x] = o;
+  sc[t] = c; so[t] = o;
   __syncthreads();
-  for (int s = 512; s > 0; s >>= 1) {
-    if ((int)threadIdx.x < s) { sc[threadIdx.x] += sc[threadIdx.x + s]; so[threadIdx.x] |= so[threadIdx.x + s]; }
+  for (int off = 1; off < 1024; off <<= 1) {          // inclusive scan (Hillis-Steele)
+    const int v = (t >= off) ? sc[t - off] : 0;
+    const int w = (t >= off) ? so[t - off] : 0;
+    __syncthreads();
+    sc[t] += v; so[t] |= w;
     __syncthreads();
   }
-  if (threadIdx.x == 0) {
-    hdr->status = so[0] ? 4 : 0;
+  const int total = sc[1023];
+  int pos = sc[t] - c;                                 // exclusive prefix
+  for (int n = r0; n < r1; ++n) {
+    bool oor;
+    const int tg = classify_target(y[n], ignore_index, V, oor);
+    if (tg >= 0) { rowmap[pos] = n; tgt_c[pos] = tg; ++pos; }
+  }
+  for (int cidx = total + t; cidx < npad; cidx += 1024) { rowmap[cidx] = -1; tgt_c[cidx] = -1; }
+  if (t == 0) {
+    hdr->status = so[1023] ? 4 : 0;
     hdr->pad0 = 0;
-    hdr->n_valid = sc[0];
+    hdr->n_valid = total;
     hdr->loss_sum = 0.f;
     hdr->pad1 = 0.f;
   }
+}
+
+// Hc[c][:] = H[rowmap[c]][:], lse_c[c] = lse[rowmap[c]]; zero rows where rowmap[c] < 0.
+// One block per compact row; rows are copied as 16-byte vectors (row_bytes % 16 == 0).
+__global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict__ H, int64_t row_bytes,
+                                                          const int* __restrict__ rowmap,
+                                                          const float* __restrict__ lse, char* __restrict__ Hc,
+                                                          float* __restrict__ lse_c) {
+  const int c = blockIdx.x;
+  const int n = rowmap[c];
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  const u32x4* src = reinterpret_cast<const u32x4*>(H + (int64_t)(n < 0 ? 0 : n) * row_bytes);
+  u32x4* dst = reinterpret_cast<u32x4*>(Hc + (int64_t)c * row_bytes);
+  const int nvec = (int)(row_bytes / 16);
+  for (int i = threadIdx.x; i < nvec; i += 256) dst[i] = (n >= 0) ? src[i] : z;
+  if (threadIdx.x == 0) lse_c[c] = (n >= 0) ? lse[n] : 0.f;
+}
+
+// dH rows of tokens that do not count are exactly +0.  One block per row.
+__global__ __launch_bounds__(256) void zero_uncounted_rows_kernel(const int64_t* __restrict__ y, int V,
+                                                                  int64_t ignore_index, char* __restrict__ dH,
+                                                                  int64_t row_bytes) {
+  const int n = blockIdx.x;
+  bool oor;
+  if (classify_target(y[n], ignore_index, V, oor) >= 0) return;
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  u32x4* dst = reinterpret_cast<u32x4*>(dH + (int64_t)n * row_bytes);
+  const int nvec = (int)(row_bytes / 16);
+  for (int i = threadIdx.x; i < nvec; i += 256) dst[i] = z;
 }
 
 // dst[c][r] = src[r0 + r][c]  for c < cols, r < rows_pad; zero where r0 + r >= rows_total.
@@ -348,35 +400,38 @@ template <> struct Pack4<bf16_t> {
 };
 
 // ------------------------------------------------------------------------------------
-// Backward, step 1: logit tile recomputed exactly as in the forward, then
-//   g = counted_row ? exp(z - lse_row) - [v == y_row] : 0      (unscaled; Gamma comes later)
+// Backward, step 1 (on the compacted rows): logit tile recomputed exactly as in the
+// forward, then
+//   g = exp(z - lse_row) - [v == y_row]            (unscaled; Gamma comes later)
 // rounded to T and written to the staging tile in both orientations:
-//   G [token - chunk_n0][vocab - chunk_v0]   (ldG  elements per row)
-//   GT[vocab - chunk_v0][token - chunk_n0]   (ldGT elements per row)
-// Padded vocabulary columns and padded / ignored token rows are written as 0.
+//   G [row - chunk_n0][vocab - chunk_v0]   (ldG  elements per row)
+//   GT[vocab - chunk_v0][row - chunk_n0]   (ldGT elements per row)
+// Padded vocabulary columns and the padding rows behind the last counted row are 0.
+// Tiles that lie entirely behind the last counted row return at once; the
+// contractions never read them.
 // ------------------------------------------------------------------------------------
 template <typename T, typename L>
 __global__ __launch_bounds__(L::THREADS) void recompute_kernel(
-    const T* __restrict__ H, const T* __restrict__ W, const int64_t* __restrict__ y, const float* __restrict__ lse,
-    int N, int d, int V, int64_t ignore_index, int nt0, int n_nt, int vt0, int n_vt,
-    T* __restrict__ G, int64_t ldG, T* __restrict__ GT, int64_t ldGT) {
+    const T* __restrict__ Hc, const T* __restrict__ W, const int* __restrict__ tgt_c,
+    const float* __restrict__ lse_c, const Header* __restrict__ hdr, int npad, int d, int V, int nt0, int n_nt,
+    int vt0, int n_vt, T* __restrict__ G, int64_t ldG, T* __restrict__ GT, int64_t ldGT) {
   extern __shared__ __align__(16) char lds[];
   const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
-  int p, q;                                    // token tile, vocabulary tile inside the chunk
+  int p, q;                                    // row tile, vocabulary tile inside the chunk
   grouped_raster(id, n_nt, n_vt, 8, p, q);
   const int n0 = (nt0 + p) * TILE, v0 = (vt0 + q) * TILE;
+  if (n0 >= (int)hdr->n_valid) return;
   const int64_t ld_bytes = (int64_t)d * sizeof(T);
   f32x16 acc[L::WM][L::WN];
-  L::run(W, ld_bytes, v0, V, H, ld_bytes, n0, N, (int)ld_bytes, lds, acc);
+  L::run(W, ld_bytes, v0, V, Hc, ld_bytes, n0, npad, (int)ld_bytes, lds, acc);
 
 #pragma unroll
   for (int j = 0; j < L::WN; ++j) {
     const int nl = p * TILE + L::tile_n(j);       // row inside the staging tile
     const int n = n0 + L::tile_n(j);
-    bool oor;
-    const int tgt = (n < N) ? classify_target(y[n], ignore_index, V, oor) : -1;
+    const int tgt = tgt_c[n];
     const bool counted = tgt >= 0;
-    const float l = (n < N) ? lse[n] : 0.f;
+    const float l = lse_c[n];
 #pragma unroll
     for (int i = 0; i < L::WM; ++i)
 #pragma unroll
@@ -399,36 +454,46 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(
 
 // ------------------------------------------------------------------------------------
 // Backward, step 2: out[n][m] (+)= sum_k A[m][k] * B[n][k]
-//   dH: A = W^T chunk [d][Vc], B = G  [tokens][Vc]  (contraction over the vocabulary chunk)
-//   dW: A = H^T       [d][Nc], B = GT [vocab][Nc]   (contraction over the token chunk)
+//   dH: A = W^T chunk [d][Vc], B = G  [rows][Vc]   (contraction over the vocabulary chunk)
+//   dW: A = Hc^T      [d][Nc], B = GT [vocab][Nc]  (contraction over the compact-row chunk)
 // M = hidden index, so each lane owns 4 consecutive output elements of one row.
 // Chunks are accumulated in fp32 in a fixed order: READ_ACC adds the running sum,
 // WRITE_ACC stores it back, WRITE_OUT multiplies by Gamma and rounds to T.
+// ROWS_COMPACT (dH): output rows are compact rows; tiles behind the last counted row
+// return at once and row c is written to out[rowmap[c]].
+// K_COMPACT (dW): the contraction runs over compact rows k_start .. k_start + k_elems and
+// stops at the last counted row (rounded up to a whole tile; that padding is zero).
 // ------------------------------------------------------------------------------------
-enum : int { READ_ACC = 1, WRITE_ACC = 2, WRITE_OUT = 4 };
+enum : int { READ_ACC = 1, WRITE_ACC = 2, WRITE_OUT = 4, ROWS_COMPACT = 8, K_COMPACT = 16 };
 
 template <typename T, typename L>
 __global__ __launch_bounds__(L::THREADS) void contract_kernel(
     const T* __restrict__ A, int64_t lda, int d, const T* __restrict__ B, int64_t ldb, int b_rows, int k_elems,
-    int n_mt, int n_nt, float* __restrict__ accbuf, int acc_row0, T* __restrict__ out, int out_row0, int out_rows,
-    int flags, const Header* __restrict__ hdr, float grad_loss, int mean) {
+    int k_start, int n_mt, int n_nt, float* __restrict__ accbuf, int acc_row0, T* __restrict__ out, int out_row0,
+    int out_rows, int flags, const Header* __restrict__ hdr, const int* __restrict__ rowmap, float grad_loss,
+    int mean) {
   extern __shared__ __align__(16) char lds[];
   const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
   int p, q;                                    // output-row tile, hidden tile
   grouped_raster(id, n_nt, n_mt, 8, p, q);
+  const int nv = (int)hdr->n_valid;
+  if ((flags & ROWS_COMPACT) && out_row0 + p * TILE >= nv) return;
+  if (flags & K_COMPACT) k_elems = max(0, min(k_elems, (nv - k_start + TILE - 1) / TILE * TILE));
   f32x16 acc[L::WM][L::WN];
   L::run(A, lda * (int64_t)sizeof(T), q * TILE, d, B, ldb * (int64_t)sizeof(T), p * TILE, b_rows,
          k_elems * (int)sizeof(T), lds, acc);
 
   float scale = grad_loss;
-  if (mean) {
-    const int64_t nv = hdr->n_valid;
-    scale = nv > 0 ? grad_loss / (float)nv : 0.f;
-  }
+  if (mean) scale = nv > 0 ? grad_loss / (float)nv : 0.f;
 #pragma unroll
   for (int j = 0; j < L::WN; ++j) {
     const int n = out_row0 + p * TILE + L::tile_n(j);
     if (n >= out_rows) continue;
+    int64_t orow = n;
+    if (flags & ROWS_COMPACT) {
+      orow = rowmap[n];
+      if (orow < 0) continue;
+    }
 #pragma unroll
     for (int i = 0; i < L::WM; ++i)
 #pragma unroll
@@ -440,8 +505,8 @@ __global__ __launch_bounds__(L::THREADS) void contract_kernel(
         if (flags & READ_ACC) v += *reinterpret_cast<const f32x4*>(ap);
         if (flags & WRITE_ACC) *reinterpret_cast<f32x4*>(ap) = v;
         if (flags & WRITE_OUT) {
-          // "+ 0.f" turns a -0 product into +0 so untouched rows come out as +0
-          Pack4<T>::store(out + (int64_t)n * d + m, v[0] * scale + 0.f, v[1] * scale + 0.f, v[2] * scale + 0.f,
+          // "+ 0.f" turns a -0 product into +0
+          Pack4<T>::store(out + orow * d + m, v[0] * scale + 0.f, v[1] * scale + 0.f, v[2] * scale + 0.f,
                           v[3] * scale + 0.f);
         }
       }
