@@ -40,8 +40,20 @@ struct Plan {
   // backward
   int n_vch, n_nch;        // chunks along vocabulary / tokens
   int vc_tiles, nc_tiles;  // largest chunk, in tiles
+  bool fast;               // tuned bf16 loop: no transposed copies
   int64_t off_Hc, off_rowmap, off_tgt, off_lsec, off_HT, off_WT, off_G, off_GT, off_dHacc, off_dWacc, bwd_bytes;
 };
+
+// The tuned bf16 loop needs K extents that are multiples of 32 elements and every tile's
+// address window below 2^31 bytes; FLCE_GENERIC=1 forces the generic loop everywhere.
+bool fast_loop_ok(const Plan& p) {
+  if (p.esize != 2 || env_int("FLCE_GENERIC", 0, 0, 1)) return false;
+  const int64_t lim = (int64_t)1 << 31;
+  const int64_t vc = (int64_t)p.vc_tiles * TILE, nc = (int64_t)p.nc_tiles * TILE;
+  const int64_t ld_hw = p.d * 2, ld_g = vc * 2;
+  return p.d % 32 == 0 && 256 * ld_hw + ld_hw < lim && 256 * ld_g + ld_g < lim &&   // K-contiguous tiles
+         (vc + 32) * ld_hw < lim && (nc + 32) * ld_hw < lim && (nc + 32) * ld_g < lim;  // K over memory rows
+}
 
 bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   if (N <= 0 || d <= 0 || V <= 0 || (d % 8) != 0) return false;
@@ -73,15 +85,17 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   p.vc_tiles = (int)ceil_div(p.n_vt, p.n_vch);
   p.nc_tiles = (int)ceil_div(p.n_rb, p.n_nch);
   const int64_t vc_pad = (int64_t)p.vc_tiles * TILE, nc_pad = (int64_t)p.nc_tiles * TILE;
+  p.fast = fast_loop_ok(p);
   o = ALIGN;
   p.off_Hc = o;     o = align_up(o + d * p.npad * p.esize, ALIGN);
   p.off_rowmap = o; o = align_up(o + p.npad * 4, ALIGN);
   p.off_tgt = o;    o = align_up(o + p.npad * 4, ALIGN);
   p.off_lsec = o;   o = align_up(o + p.npad * 4, ALIGN);
-  p.off_HT = o;     o = align_up(o + d * p.npad * p.esize, ALIGN);
-  p.off_WT = o;     o = align_up(o + d * vc_pad * p.esize, ALIGN);
   p.off_G = o;      o = align_up(o + nc_pad * vc_pad * p.esize, ALIGN);
-  p.off_GT = o;     o = align_up(o + nc_pad * vc_pad * p.esize, ALIGN);
+  // K-contiguous copies, only for main loops that cannot read an operand across memory rows
+  p.off_HT = o;     if (!p.fast) o = align_up(o + d * p.npad * p.esize, ALIGN);
+  p.off_WT = o;     if (!p.fast) o = align_up(o + d * vc_pad * p.esize, ALIGN);
+  p.off_GT = o;     if (!p.fast) o = align_up(o + nc_pad * vc_pad * p.esize, ALIGN);
   p.off_dHacc = o;  if (p.n_vch > 1) o = align_up(o + N * d * 4, ALIGN);
   p.off_dWacc = o;  if (p.n_nch > 1) o = align_up(o + vc_pad * d * 4, ALIGN);
   p.bwd_bytes = o;
@@ -129,20 +143,15 @@ hipError_t prepare_kernels() {
   hipError_t e;
   if ((e = allow_big_lds(fwd_tiles_kernel<T, L>, L::LDS)) != hipSuccess) return e;
   if ((e = allow_big_lds(recompute_kernel<T, L>, L::LDS)) != hipSuccess) return e;
-  if ((e = allow_big_lds(contract_kernel<T, L>, L::LDS)) != hipSuccess) return e;
+  if constexpr (L::TRANSPOSING) {
+    if ((e = allow_big_lds(contract_kernel<T, L, OPS_DH_TR>, L::LDS)) != hipSuccess) return e;
+    if ((e = allow_big_lds(contract_kernel<T, L, OPS_DW_TR>, L::LDS)) != hipSuccess) return e;
+  } else {
+    if ((e = allow_big_lds(contract_kernel<T, L, OPS_KC>, L::LDS)) != hipSuccess) return e;
+  }
   return hipSuccess;
 }
 
-// The tuned bf16 loop needs K extents that are multiples of 32 elements and row
-// pitches below 2^23 bytes; FLCE_GENERIC=1 forces the generic loop everywhere.
-bool fast_loop_ok(const Plan& p) {
-  if (p.esize != 2 || env_int("FLCE_GENERIC", 0, 0, 1)) return false;
-  const int64_t lim = (int64_t)1 << 23;
-  return p.d % 32 == 0 && p.d * 2 < lim && p.npad * 2 < lim && (int64_t)p.vc_tiles * TILE * 2 < lim &&
-         (int64_t)p.nc_tiles * TILE * 2 < lim;
-}
-
-// The attribute is per device; set it on every call's current device (a cheap host-side call).
 template <typename T, typename L>
 flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t* y, int64_t ignore_index,
                       int mean, float* loss_out, float* lse_out, char* ws, hipStream_t st) {
@@ -196,15 +205,17 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     gather_rows_kernel<<<npad, 256, 0, st>>>(static_cast<const char*>(H), row_bytes, rowmap, lse,
                                              reinterpret_cast<char*>(Hc), lse_c);
     zero_uncounted_rows_kernel<<<N, 256, 0, st>>>(y, V, ignore_index, static_cast<char*>(dH), row_bytes);
-    // Hc^T [d][npad]: K-contiguous operand of the dW contraction
-    transpose_pad_kernel<U><<<dim3((unsigned)ceil_div(p.npad, 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
-        reinterpret_cast<const U*>(Hc), d, npad, 0, d, reinterpret_cast<U*>(HT), p.npad, npad);
+    if constexpr (!L::TRANSPOSING) {
+      // Hc^T [d][npad]: K-contiguous operand of the dW contraction
+      transpose_pad_kernel<U><<<dim3((unsigned)ceil_div(p.npad, 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
+          reinterpret_cast<const U*>(Hc), d, npad, 0, d, reinterpret_cast<U*>(HT), p.npad, npad);
+    }
   }
 
   for (int vc = 0; vc < p.n_vch; ++vc) {
     const int vt0 = (int)((int64_t)vc * p.n_vt / p.n_vch), vt1 = (int)((int64_t)(vc + 1) * p.n_vt / p.n_vch);
     const int n_vt = vt1 - vt0;
-    {
+    if constexpr (!L::TRANSPOSING) {
       // W^T chunk [d][vc_pad]: K-contiguous operand of the dH contraction
       ProfScope ps(FLCE_PROF_BWD_PREP, st);
       transpose_pad_kernel<U><<<dim3((unsigned)(n_vt * TILE / 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
@@ -225,9 +236,14 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
         if (nc > 0) flags |= READ_ACC;
         flags |= (nc + 1 < p.n_nch) ? WRITE_ACC : WRITE_OUT;
         ProfScope ps(FLCE_PROF_CONTRACT_DW, st);
-        contract_kernel<T, L><<<n_vt * n_mt, L::THREADS, L::LDS, st>>>(
-            HT + (int64_t)nt0 * TILE, p.npad, d, GT, nc_pad, n_vt * TILE, n_nt * TILE, nt0 * TILE, n_mt, n_vt, dWacc,
-            vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags, hdr, rowmap, grad_loss, mean);
+        if constexpr (L::TRANSPOSING)
+          contract_kernel<T, L, OPS_DW_TR><<<n_vt * n_mt, L::THREADS, L::LDS, st>>>(
+              Hc + (int64_t)nt0 * TILE * d, d, npad - nt0 * TILE, d, G, vc_pad, n_nt * TILE, n_nt * TILE, nt0 * TILE,
+              n_mt, n_vt, dWacc, vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags, hdr, rowmap, grad_loss, mean);
+        else
+          contract_kernel<T, L, OPS_KC><<<n_vt * n_mt, L::THREADS, L::LDS, st>>>(
+              HT + (int64_t)nt0 * TILE, p.npad, 0, d, GT, nc_pad, n_vt * TILE, n_nt * TILE, nt0 * TILE, n_mt, n_vt,
+              dWacc, vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags, hdr, rowmap, grad_loss, mean);
       }
       // dH[row chunk] += G . W^T[:, vocab chunk]^T     (contraction over the vocabulary chunk)
       {
@@ -235,9 +251,15 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
         if (vc > 0) flags |= READ_ACC;
         flags |= (vc + 1 < p.n_vch) ? WRITE_ACC : WRITE_OUT;
         ProfScope ps(FLCE_PROF_CONTRACT_DH, st);
-        contract_kernel<T, L><<<n_nt * n_mt, L::THREADS, L::LDS, st>>>(
-            WT, vc_pad, d, G, vc_pad, n_nt * TILE, n_vt * TILE, 0, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH),
-            nt0 * TILE, npad, flags, hdr, rowmap, grad_loss, mean);
+        if constexpr (L::TRANSPOSING)
+          contract_kernel<T, L, OPS_DH_TR><<<n_nt * n_mt, L::THREADS, L::LDS, st>>>(
+              static_cast<const T*>(W) + (int64_t)vt0 * TILE * d, d, V - vt0 * TILE, d, G, vc_pad, n_nt * TILE,
+              n_vt * TILE, 0, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH), nt0 * TILE, npad, flags, hdr, rowmap,
+              grad_loss, mean);
+        else
+          contract_kernel<T, L, OPS_KC><<<n_nt * n_mt, L::THREADS, L::LDS, st>>>(
+              WT, vc_pad, 0, d, G, vc_pad, n_nt * TILE, n_vt * TILE, 0, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH),
+              nt0 * TILE, npad, flags, hdr, rowmap, grad_loss, mean);
       }
     }
   }
@@ -287,7 +309,7 @@ flce_status flce_forward(const void* H, const void* W, const int64_t* targets, i
   const int mean = reduction == FLCE_REDUCE_MEAN;
   char* ws = static_cast<char*>(workspace);
   if (dt == FLCE_DTYPE_BF16) {
-    if (flce::fast_loop_ok(p))
+    if (p.fast)
       return flce::forward_t<flce::bf16_t, flce::FastLoop>(p, H, W, targets, ignore_index, mean, loss_out, lse_out,
                                                            ws, st);
     return flce::forward_t<flce::bf16_t, flce::GenericLoop<flce::bf16_t>>(p, H, W, targets, ignore_index, mean,
@@ -314,7 +336,7 @@ flce_status flce_backward(const void* H, const void* W, const int64_t* targets, 
   const int mean = reduction == FLCE_REDUCE_MEAN;
   char* ws = static_cast<char*>(workspace);
   if (dt == FLCE_DTYPE_BF16) {
-    if (flce::fast_loop_ok(p))
+    if (p.fast)
       return flce::backward_t<flce::bf16_t, uint16_t, flce::FastLoop>(p, H, W, targets, lse, ignore_index, mean,
                                                                       grad_loss, dH_out, dW_out, ws, st);
     return flce::backward_t<flce::bf16_t, uint16_t, flce::GenericLoop<flce::bf16_t>>(

@@ -27,6 +27,7 @@ namespace flce {
 template <typename T>
 struct GenericLoop {      // any dtype, any K that is a multiple of 16 bytes; 8 wavefronts 2 x 4
   static constexpr int THREADS = flce::THREADS, WM = flce::WM, WN = flce::WN, LDS = LDS_BYTES;
+  static constexpr bool TRANSPOSING = false;  // needs K-contiguous copies of every operand
   static __device__ __forceinline__ int tile_m(int i, int r) { return flce::tile_m(i, r); }
   static __device__ __forceinline__ int tile_n(int j) { return flce::tile_n(j); }
   static __device__ __forceinline__ int slot() {
@@ -43,15 +44,16 @@ struct GenericLoop {      // any dtype, any K that is a multiple of 16 bytes; 8 
 
 struct FastLoop {         // bf16, K a multiple of 32 elements; 4 wavefronts 2 x 2, global -> LDS DMA
   static constexpr int THREADS = fast::THREADS, WM = fast::WM, WN = fast::WN, LDS = fast::LDS_BYTES;
+  static constexpr bool TRANSPOSING = true;   // can take an operand whose K index runs over memory rows
   static __device__ __forceinline__ int tile_m(int i, int r) { return fast::tile_m(i, r); }
   static __device__ __forceinline__ int tile_n(int j) { return fast::tile_n(j); }
   static __device__ __forceinline__ int slot() { return fast::slot_of_lane(); }
   static __device__ __forceinline__ void run(const void* A, int64_t lda_bytes, int a_row0, int a_rows, const void* B,
                                              int64_t ldb_bytes, int b_row0, int b_rows, int k_bytes, char* lds,
                                              f32x16 (&acc)[WM][WN]) {
-    const fast::Src As{static_cast<const char*>(A), lda_bytes, a_row0, a_rows};
-    const fast::Src Bs{static_cast<const char*>(B), ldb_bytes, b_row0, b_rows};
-    fast::mainloop(As, Bs, k_bytes, lds, acc);
+    const fast::Operand As{static_cast<const char*>(A), lda_bytes, a_row0, a_rows, 0};
+    const fast::Operand Bs{static_cast<const char*>(B), ldb_bytes, b_row0, b_rows, 0};
+    fast::mainloop<fast::KC, fast::KC>(As, Bs, k_bytes / 2, lds, acc);
   }
 };
 
@@ -403,8 +405,9 @@ template <> struct Pack4<bf16_t> {
 // Backward, step 1 (on the compacted rows): logit tile recomputed exactly as in the
 // forward, then
 //   g = exp(z - lse_row) - [v == y_row]            (unscaled; Gamma comes later)
-// rounded to T and written to the staging tile in both orientations:
+// rounded to T and written to the staging tile
 //   G [row - chunk_n0][vocab - chunk_v0]   (ldG  elements per row)
+// and, for main loops that need K-contiguous operands, also transposed:
 //   GT[vocab - chunk_v0][row - chunk_n0]   (ldGT elements per row)
 // Padded vocabulary columns and the padding rows behind the last counted row are 0.
 // Tiles that lie entirely behind the last counted row return at once; the
@@ -446,8 +449,10 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(
         }
         const int vl = q * TILE + mloc;
         Pack4<T>::store(G + (int64_t)nl * ldG + vl, g[0], g[1], g[2], g[3]);
+        if (!L::TRANSPOSING) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) GT[(int64_t)(vl + e) * ldGT + nl] = Pack4<T>::one(g[e]);
+          for (int e = 0; e < 4; ++e) GT[(int64_t)(vl + e) * ldGT + nl] = Pack4<T>::one(g[e]);
+        }
       }
   }
 }
@@ -464,12 +469,18 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(
 // K_COMPACT (dW): the contraction runs over compact rows k_start .. k_start + k_elems and
 // stops at the last counted row (rounded up to a whole tile; that padding is zero).
 // ------------------------------------------------------------------------------------
+//
+// OPS selects how the operands lie in memory:
+//   OPS_KC    : A[m][k], B[n][k] both K-contiguous (the transposed copies W^T, Hc^T, GT)
+//   OPS_DH_TR : A = W rows of the vocabulary chunk [k][m] (K over memory rows), B = G [n][k]
+//   OPS_DW_TR : A = Hc rows of the row chunk [k][m], B = G rows of the row chunk [k][n]
 enum : int { READ_ACC = 1, WRITE_ACC = 2, WRITE_OUT = 4, ROWS_COMPACT = 8, K_COMPACT = 16 };
+enum : int { OPS_KC = 0, OPS_DH_TR = 1, OPS_DW_TR = 2 };
 
-template <typename T, typename L>
+template <typename T, typename L, int OPS>
 __global__ __launch_bounds__(L::THREADS) void contract_kernel(
-    const T* __restrict__ A, int64_t lda, int d, const T* __restrict__ B, int64_t ldb, int b_rows, int k_elems,
-    int k_start, int n_mt, int n_nt, float* __restrict__ accbuf, int acc_row0, T* __restrict__ out, int out_row0,
+    const T* __restrict__ A, int64_t lda, int a_krows, int d, const T* __restrict__ B, int64_t ldb, int b_rows,
+    int k_elems, int k_start, int n_mt, int n_nt, float* __restrict__ accbuf, int acc_row0, T* __restrict__ out, int out_row0,
     int out_rows, int flags, const Header* __restrict__ hdr, const int* __restrict__ rowmap, float grad_loss,
     int mean) {
   extern __shared__ __align__(16) char lds[];
@@ -480,8 +491,21 @@ __global__ __launch_bounds__(L::THREADS) void contract_kernel(
   if ((flags & ROWS_COMPACT) && out_row0 + p * TILE >= nv) return;
   if (flags & K_COMPACT) k_elems = max(0, min(k_elems, (nv - k_start + TILE - 1) / TILE * TILE));
   f32x16 acc[L::WM][L::WN];
-  L::run(A, lda * (int64_t)sizeof(T), q * TILE, d, B, ldb * (int64_t)sizeof(T), p * TILE, b_rows,
-         k_elems * (int)sizeof(T), lds, acc);
+  if constexpr (OPS == OPS_KC) {
+    L::run(A, lda * (int64_t)sizeof(T), q * TILE, d, B, ldb * (int64_t)sizeof(T), p * TILE, b_rows,
+           k_elems * (int)sizeof(T), lds, acc);
+  } else {
+    // A: K rows start at A (a_rows = b_rows_or_k valid from there), window of 256 hidden columns at q
+    const int width = max(0, min(TILE, d - q * TILE)) * 2;
+    const fast::Operand As{reinterpret_cast<const char*>(A) + (int64_t)q * TILE * 2, lda * 2, 0, a_krows, width};
+    if constexpr (OPS == OPS_DH_TR) {
+      const fast::Operand Bs{reinterpret_cast<const char*>(B), ldb * 2, p * TILE, b_rows, 0};
+      fast::mainloop<fast::KR, fast::KC>(As, Bs, k_elems, lds, acc);
+    } else {
+      const fast::Operand Bs{reinterpret_cast<const char*>(B) + (int64_t)p * TILE * 2, ldb * 2, 0, b_rows, TILE * 2};
+      fast::mainloop<fast::KR, fast::KR>(As, Bs, k_elems, lds, acc);
+    }
+  }
 
   float scale = grad_loss;
   if (mean) scale = nv > 0 ? grad_loss / (float)nv : 0.f;

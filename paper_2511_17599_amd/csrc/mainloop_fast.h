@@ -4,22 +4,31 @@
 //
 //   * Operand tiles go from global memory straight into LDS (buffer_load ... lds,
 //     16 bytes per lane), four stages of 32 bf16 of K deep, so a tile is requested
-//     two to three K steps before it is read.  Rows past the end of a
-//     tensor are zero-filled by the buffer's range check.
-//   * LDS tile layout [256 rows][64 bytes]; the 16-byte chunk index is XOR-ed with
-//     (row / 4) % 4, which spreads the 16 consecutive rows that a quarter wavefront
-//     reads in one cycle over all 64 banks.  The DMA writes LDS linearly, so the
-//     swizzle is applied to the global address each lane fetches from.
+//     two to three K steps before it is read.  Rows past the end of a tensor are
+//     zero-filled by the buffer's range check.
+//   * Each operand may be stored either way round in memory:
+//       KC ("K contiguous"): 256 tile rows, each with its 32 K values adjacent (64 bytes).
+//           LDS tile [256][64 B]; fragments are plain 128-bit LDS reads.
+//       KR ("K rows"): the 32 K values of a tile row lie in 32 different memory rows, and
+//           one memory row holds the 256 tile rows' values side by side (512 bytes).
+//           LDS tile [32][512 B]; fragments come from the transposing LDS read
+//           (ds_read_b64_tr_b16: 16 lanes hand in four K rows of 4 x 8 bytes and each
+//           lane gets back 4 consecutive K values of one tile row).
+//     This lets dH = G.W and dW = G^T.H read G, W and H where they are, with no
+//     transposed copies.
+//   * LDS swizzles (applied on the global side, because the DMA writes LDS linearly):
+//     KC: 16-byte chunk index ^ (row / 4) % 4; KR: 64-byte chunk index ^ (k % 4).  Both
+//     spread what one LDS instruction touches in a cycle over all 64 banks.
 //   * Fragments are double buffered in registers and the single barrier per K step
 //     sits between the two MFMA groups of the step: LDS latency and the barrier wait
 //     are both covered by 16 independent MFMAs.
-//   * The instruction order inside a K step is written out by hand (one LDS read or
-//     one global request between consecutive MFMAs, pinned with scheduling barriers):
+//   * The instruction order inside a K step is pinned by hand (LDS reads and global
+//     requests spread between consecutive MFMAs, fenced with scheduling barriers):
 //     with one wavefront per SIMD a burst of memory instructions stalls the MFMA
-//     stream, and the 8 requests of a tile are spread over the whole step.
+//     stream.
 //
-// Requires K * 2 bytes to be a multiple of 64 and row pitches below 2^23 bytes; the
-// generic loop in tile_mma.h covers everything else.
+// Requires the K extent to be a multiple of 32 elements and offsets inside one tile's
+// address window below 2^31; the generic loop in tile_mma.h covers everything else.
 #pragma once
 #include "tile_mma.h"
 
@@ -28,29 +37,68 @@ namespace fast {
 
 constexpr int THREADS = 256;
 constexpr int WM = 4, WN = 4;
-constexpr int BKB = 64;                   // bytes of K per stage and row
+constexpr int BK = 32;                    // K elements per stage
 constexpr int NS = 4;                     // stages
-constexpr int OPER = TILE * BKB;          // 16 KiB per operand per stage
+constexpr int OPER = TILE * BK * 2;       // 16 KiB per operand per stage (either layout)
 constexpr int STAGE = 2 * OPER;
 constexpr int LDS_BYTES = NS * STAGE;     // 128 KiB
 constexpr int LOADS_PER_TILE = 8;         // buffer_load...lds instructions per wavefront per stage
 
-typedef __attribute__((address_space(3))) void lds_void;
+enum : int { KC = 0, KR = 1 };
 
-struct Src {
-  const char* base;     // first byte of row 0 of the tensor (K offset already applied)
-  int64_t ld_bytes;     // row pitch
-  int row0;             // first row of this tile
-  int rows;             // valid rows in the tensor
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+// One operand of the contraction.
+//   KC: base = first byte of row 0 of the tensor at the first K element; row0 = first tile
+//       row; rows = valid rows of the tensor; width_bytes unused.
+//   KR: base = first byte of K row 0 at the tile's first column; rows = valid K rows from
+//       there; width_bytes = valid bytes of the tile's 512-byte column window (columns
+//       beyond it may read as the next row's data: the caller masks what they produce).
+struct Operand {
+  const char* base;
+  int64_t ld_bytes;
+  int row0;
+  int rows;
+  int width_bytes;
 };
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const Src& s, int k_bytes) {
-  int vr = min(TILE, s.rows - s.row0);
-  if (vr < 0) vr = 0;
-  // bytes from the tile's first row to the end of its last valid row
-  const uint32_t n = vr > 0 ? (uint32_t)((int64_t)(vr - 1) * s.ld_bytes + k_bytes) : 0u;
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(s.base) + (int64_t)s.row0 * s.ld_bytes, 0, (int)n,
-                                           0x00020000);
+// The global -> LDS request is issued through inline assembly: as an intrinsic the compiler
+// treats it as a store that may alias every later LDS read it cannot disambiguate (the
+// transposing reads among them) and waits for vmcnt(0) before each, which serialises the
+// pipeline.  Here the only consumers are separated from the DMA by the explicit vmcnt
+// wait + barrier of the main loop.  M0 carries the LDS destination of the wavefront.
+__device__ __forceinline__ void dma16(u32x4 rsrc, uint32_t lds_addr, int voffset, int soffset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+               : "memory", "m0");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const char* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
+
+template <int LAYOUT>
+__device__ __forceinline__ u32x4 make_rsrc(const Operand& s, int k_elems) {
+  uint32_t n = 0;
+  const char* b = s.base;
+  if (LAYOUT == KC) {
+    int vr = min(TILE, s.rows - s.row0);
+    if (vr > 0) n = (uint32_t)((int64_t)(vr - 1) * s.ld_bytes + k_elems * 2);
+    b += (int64_t)s.row0 * s.ld_bytes;
+  } else {
+    const int kr = min(s.rows, k_elems);
+    if (kr > 0 && s.width_bytes > 0) n = (uint32_t)((int64_t)(kr - 1) * s.ld_bytes + s.width_bytes);
+  }
+  // raw buffer descriptor: 48-bit base, stride 0, num_records in bytes, untyped 32-bit data format
+  const uint64_t addr = (uint64_t)(uintptr_t)b;
+  u32x4 r = {(uint32_t)addr, (uint32_t)(addr >> 32) & 0xFFFFu, n, 0x00020000u};
+  r[0] = __builtin_amdgcn_readfirstlane(r[0]);
+  r[1] = __builtin_amdgcn_readfirstlane(r[1]);
+  r[2] = __builtin_amdgcn_readfirstlane(r[2]);
+  return r;
 }
 
 __device__ __forceinline__ int tile_m(int i, int r) {
@@ -61,7 +109,7 @@ __device__ __forceinline__ int tile_n(int j) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   return (wave & 1) * 128 + j * 32 + (lane & 31);
 }
-__device__ __forceinline__ int slot_of_lane() {      // which of the 4 lanes sharing a token column this is
+__device__ __forceinline__ int slot_of_lane() {      // which of the 4 lanes sharing an N column this is
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   return (wave >> 1) * 2 + (lane >> 5);
 }
@@ -74,41 +122,83 @@ __device__ __forceinline__ void wait_vm_and_lds() {
   __builtin_amdgcn_s_waitcnt((hi << 14) | (0x0 << 8) | (0x7 << 4) | lo);
 }
 
+// Global -> LDS requests of one operand: 4 per wavefront per stage, 1 KiB each, written
+// linearly into this wavefront's 4 KiB slice of the operand tile.
+template <int LAYOUT>
 struct Loader {
-  __amdgpu_buffer_rsrc_t ra, rb;
-  int va[4], vb[4];       // per-lane byte offsets of the 4 requests of each operand
-  int lds_wave;           // LDS byte offset of this wavefront's first destination row
-  __device__ __forceinline__ void init(const Src& A, const Src& B, int k_bytes) {
-    ra = make_rsrc(A, k_bytes);
-    rb = make_rsrc(B, k_bytes);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    lds_wave = wave * 64 * BKB;
+  u32x4 rs;
+  int v[4];               // per-lane byte offsets of the 4 requests (K tile 0)
+  int k_step;             // KC: bytes of K per stage (scalar offset); KR: bytes of 32 K rows (added per lane)
+  __device__ __forceinline__ void init(const Operand& s, int k_elems) {
+    rs = make_rsrc<LAYOUT>(s, k_elems);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int row = wave * 64 + i * 16 + (lane >> 2);
-      const int chunk = (lane & 3) ^ ((row >> 2) & 3);
-      va[i] = (int)(row * A.ld_bytes) + chunk * 16;
-      vb[i] = (int)(row * B.ld_bytes) + chunk * 16;
+      if (LAYOUT == KC) {
+        const int row = wave * 64 + i * 16 + (lane >> 2);
+        const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+        v[i] = (int)(row * s.ld_bytes) + chunk * 16;
+      } else {
+        const int krow = wave * 8 + i * 2 + (lane >> 5);
+        const int off = ((lane & 31) * 16) ^ ((krow & 3) << 6);
+        v[i] = (int)(krow * s.ld_bytes) + off;
+      }
+    }
+    k_step = LAYOUT == KC ? BK * 2 : (int)(BK * s.ld_bytes);
+  }
+  // request i of K tile kt into `dst` (this wavefront's slice of the operand tile of some stage)
+  __device__ __forceinline__ void issue(int i, char* dst, int kt) const {
+    if (LAYOUT == KC)
+      dma16(rs, lds_address(dst + i * 1024), v[i], kt * k_step);
+    else   // the K advance moves to other rows: keep it in the per-lane offset, which the range check covers
+      dma16(rs, lds_address(dst + i * 1024), v[i] + kt * k_step, 0);
+  }
+};
+
+// Per-lane LDS byte offsets of the fragment reads of one operand; wsub = which 128-row
+// half of the tile this wavefront works on.
+template <int LAYOUT>
+struct FragAddr {
+  int o[4];   // KC: o[ks] for the two MFMA K steps (o[2], o[3] unused); KR: o[i] for the 4 blocks
+  __device__ __forceinline__ void init(int wsub) {
+    const int lane = threadIdx.x & 63;
+    if (LAYOUT == KC) {
+      const int l32 = lane & 31, half = lane >> 5, sw = (l32 >> 2) & 3;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) o[ks] = (wsub * 128 + l32) * 64 + (((ks * 2 + half) ^ sw) << 4);
+      o[2] = o[3] = 0;
+    } else {
+      const int e = (lane >> 2) & 3, q = lane & 3, mg = (lane >> 4) & 1, kh = lane >> 5;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[i] = (8 * kh + e) * 512 + wsub * 256 + 64 * (i ^ e) + 32 * mg + 8 * q;
     }
   }
-  __device__ __forceinline__ void issue(char* lds, int stage, int k0_bytes) const {
-    char* dst = lds + stage * STAGE + lds_wave;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void*)(dst + i * 16 * BKB), 16, va[i], k0_bytes, 0, 0);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void*)(dst + OPER + i * 16 * BKB), 16, vb[i], k0_bytes, 0, 0);
-  }
+  static constexpr int READS = LAYOUT == KC ? 4 : 8;   // LDS reads per MFMA K step
 };
 
 struct Frags {
   bf16x8 a[WM], b[WN];
 };
 
-// acc = A_tile . B_tile^T over k_bytes of K.  On return all wavefronts have passed a
-// barrier after their last LDS read, so the caller may reuse `lds`.
-__device__ __forceinline__ void mainloop(const Src& A, const Src& B, int k_bytes, char* lds, f32x16 (&acc)[WM][WN]) {
+// Read number t (0 .. READS-1) of the fragments of one operand for MFMA K step ks of a stage.
+template <int LAYOUT>
+__device__ __forceinline__ void read_frag(bf16x8 (&f)[4], const FragAddr<LAYOUT>& fa, const char* tile, int ks, int t) {
+  if (LAYOUT == KC) {
+    f[t] = *reinterpret_cast<const bf16x8*>(tile + fa.o[ks] + t * 32 * 64);
+  } else {
+    const int i = t >> 1, r = t & 1;
+    const s16x4 h = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fa.o[i] + (16 * ks + 4 * r) * 512));
+    const bf16x4 hb = __builtin_bit_cast(bf16x4, h);
+    if (r == 0) { f[i][0] = hb[0]; f[i][1] = hb[1]; f[i][2] = hb[2]; f[i][3] = hb[3]; }
+    else        { f[i][4] = hb[0]; f[i][5] = hb[1]; f[i][6] = hb[2]; f[i][7] = hb[3]; }
+  }
+}
+
+// acc = A_tile . B_tile^T over k_elems of K (a multiple of 32).  On return all wavefronts
+// have passed a barrier after their last LDS read, so the caller may reuse `lds`.
+template <int LA, int LB>
+__device__ __forceinline__ void mainloop(const Operand& A, const Operand& B, int k_elems, char* lds,
+                                         f32x16 (&acc)[WM][WN]) {
 #pragma unroll
   for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -116,63 +206,61 @@ __device__ __forceinline__ void mainloop(const Src& A, const Src& B, int k_bytes
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int KT = k_bytes / BKB;
-  Loader ld;
-  ld.init(A, B, k_bytes);
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int l32 = lane & 31, half = lane >> 5;
-  const int sw = (l32 >> 2) & 3;
-  // byte offsets of this lane's fragment inside an operand tile for the two MFMA K steps of a stage
-  int offA[2], offB[2];
-#pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
-    const int c = ((ks * 2 + half) ^ sw) << 4;
-    offA[ks] = ((wave >> 1) * 128 + l32) * BKB + c;
-    offB[ks] = ((wave & 1) * 128 + l32) * BKB + c;
-  }
+  const int KT = k_elems / BK;
+  Loader<LA> la;
+  Loader<LB> lb;
+  la.init(A, k_elems);
+  lb.init(B, k_elems);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  FragAddr<LA> fa;
+  FragAddr<LB> fb;
+  fa.init(wave >> 1);
+  fb.init(wave & 1);
+  const int lds_wave = wave * 4096;
+  constexpr int RA = FragAddr<LA>::READS, RB = FragAddr<LB>::READS, RT = RA + RB;
 
   // prologue: tiles 0..2 requested, tile 0 landed
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
-    if (s < KT) ld.issue(lds, s, s * BKB);
+    if (s < KT) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) la.issue(i, lds + s * STAGE + lds_wave, s);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) lb.issue(i, lds + s * STAGE + OPER + lds_wave, s);
+    }
   if (KT > 2) wait_vm_and_lds<2 * LOADS_PER_TILE>();
   else if (KT > 1) wait_vm_and_lds<LOADS_PER_TILE>();
   else wait_vm_and_lds<0>();
   __builtin_amdgcn_s_barrier();
   Frags f0, f1;
 #pragma unroll
-  for (int i = 0; i < WM; ++i) f0.a[i] = *reinterpret_cast<const bf16x8*>(lds + offA[0] + i * 32 * BKB);
+  for (int t = 0; t < RA; ++t) read_frag<LA>(f0.a, fa, lds, 0, t);
 #pragma unroll
-  for (int j = 0; j < WN; ++j) f0.b[j] = *reinterpret_cast<const bf16x8*>(lds + OPER + offB[0] + j * 32 * BKB);
+  for (int t = 0; t < RB; ++t) read_frag<LB>(f0.b, fb, lds + OPER, 0, t);
 
-#define FLCE_SB __builtin_amdgcn_sched_barrier(0);
-#define FLCE_MF(F, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F.a[i], F.b[j], acc[i][j], 0, 0, 0);
-#define FLCE_RA(F, i, st, ks) F.a[i] = *reinterpret_cast<const bf16x8*>((st) + offA[ks] + (i) * 32 * BKB);
-#define FLCE_RB(F, j, st, ks) F.b[j] = *reinterpret_cast<const bf16x8*>((st) + OPER + offB[ks] + (j) * 32 * BKB);
-#define FLCE_LA(i) \
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.ra, (lds_void*)(dstn + (i) * 16 * BKB), 16, ld.va[i], k0n, 0, 0);
-#define FLCE_LB(i) \
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.rb, (lds_void*)(dstn + OPER + (i) * 16 * BKB), 16, ld.vb[i], k0n, 0, 0);
-// One half of a K step: the 16 MFMAs of fragment set FM, with the 8 LDS reads that fill
-// fragment set FR (from stage ST, MFMA K step KS) and 4 global requests (LX) in between.
-#define FLCE_HALF(FM, FR, ST, KS, LX)                               \
-  FLCE_MF(FM, 0, 0) FLCE_RA(FR, 0, ST, KS) FLCE_SB                  \
-  FLCE_MF(FM, 0, 1) FLCE_RA(FR, 1, ST, KS) FLCE_SB                  \
-  FLCE_MF(FM, 0, 2) LX(0) FLCE_SB                                   \
-  FLCE_MF(FM, 0, 3) FLCE_SB                                         \
-  FLCE_MF(FM, 1, 0) FLCE_RA(FR, 2, ST, KS) FLCE_SB                  \
-  FLCE_MF(FM, 1, 1) FLCE_RA(FR, 3, ST, KS) FLCE_SB                  \
-  FLCE_MF(FM, 1, 2) LX(1) FLCE_SB                                   \
-  FLCE_MF(FM, 1, 3) FLCE_SB                                         \
-  FLCE_MF(FM, 2, 0) FLCE_RB(FR, 0, ST, KS) FLCE_SB                  \
-  FLCE_MF(FM, 2, 1) FLCE_RB(FR, 1, ST, KS) FLCE_SB                  \
-  FLCE_MF(FM, 2, 2) LX(2) FLCE_SB                                   \
-  FLCE_MF(FM, 2, 3) FLCE_SB                                         \
-  FLCE_MF(FM, 3, 0) FLCE_RB(FR, 2, ST, KS) FLCE_SB                  \
-  FLCE_MF(FM, 3, 1) FLCE_RB(FR, 3, ST, KS) FLCE_SB                  \
-  FLCE_MF(FM, 3, 2) LX(3) FLCE_SB                                   \
-  FLCE_MF(FM, 3, 3) FLCE_SB
-#define FLCE_NOLOAD(i)
+  // One half of a K step: the 16 MFMAs of fragment set FM; between them the LDS reads that
+  // fill fragment set FR (stage `st`, MFMA K step ks) and, if load_kt >= 0, the 4 global
+  // requests of operand `which` (0 = A, 1 = B) of K tile load_kt into stage `lst`.
+  auto half_step = [&](const Frags& FM, Frags& FR, const char* st, int ks, int which, int load_kt, char* lst) {
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      acc[s >> 2][s & 3] =
+          __builtin_amdgcn_mfma_f32_32x32x16_bf16(FM.a[s >> 2], FM.b[s & 3], acc[s >> 2][s & 3], 0, 0, 0);
+      // reads t with t * 16 / RT == s: spread evenly over the 16 slots
+#pragma unroll
+      for (int t = 0; t < RT; ++t)
+        if (t * 16 / RT == s) {
+          if (t < RA) read_frag<LA>(FR.a, fa, st, ks, t);
+          else read_frag<LB>(FR.b, fb, st + OPER, ks, t - RA);
+        }
+      if ((s & 3) == 2 && load_kt >= 0) {
+        if (which == 0) la.issue(s >> 2, lst + lds_wave, load_kt);
+        else lb.issue(s >> 2, lst + OPER + lds_wave, load_kt);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
 
   // Steady state: K step kt computes tile kt and requests tile kt+3 into the stage that
   // was freed by the barrier of step kt-1.
@@ -180,39 +268,26 @@ __device__ __forceinline__ void mainloop(const Src& A, const Src& B, int k_bytes
   for (; kt + NS - 1 < KT; ++kt) {
     const char* cur = lds + (kt & (NS - 1)) * STAGE;
     const char* nxt = lds + ((kt + 1) & (NS - 1)) * STAGE;
-    char* dstn = lds + ((kt + NS - 1) & (NS - 1)) * STAGE + ld.lds_wave;
-    const int k0n = (kt + NS - 1) * BKB;
-    FLCE_SB
-    FLCE_HALF(f0, f1, cur, 1, FLCE_LA)
+    char* lst = lds + ((kt + NS - 1) & (NS - 1)) * STAGE;
+    half_step(f0, f1, cur, 1, 0, kt + NS - 1, lst);
     // tile kt+1 has landed once only tile kt+2 and the first half of tile kt+3 are in flight;
     // lgkmcnt(0): this wavefront holds all its fragments of tile kt
     wait_vm_and_lds<LOADS_PER_TILE + LOADS_PER_TILE / 2>();
     __builtin_amdgcn_s_barrier();
-    FLCE_SB
-    FLCE_HALF(f1, f0, nxt, 0, FLCE_LB)
+    half_step(f1, f0, nxt, 0, 1, kt + NS - 1, lst);
   }
   // Drain: the last (up to NS-1) tiles, nothing left to request.
   for (; kt < KT; ++kt) {
     const char* cur = lds + (kt & (NS - 1)) * STAGE;
     const char* nxt = lds + ((kt + 1) & (NS - 1)) * STAGE;   // past the last tile: stale data, never used
-    FLCE_SB
-    FLCE_HALF(f0, f1, cur, 1, FLCE_NOLOAD)
+    half_step(f0, f1, cur, 1, 0, -1, nullptr);
     if (kt + 2 < KT) wait_vm_and_lds<LOADS_PER_TILE>();
     else wait_vm_and_lds<0>();
     __builtin_amdgcn_s_barrier();
-    FLCE_SB
-    FLCE_HALF(f1, f0, nxt, 0, FLCE_NOLOAD)
+    half_step(f1, f0, nxt, 0, 1, -1, nullptr);
   }
   wait_vm_and_lds<0>();
   __builtin_amdgcn_s_barrier();
-#undef FLCE_SB
-#undef FLCE_MF
-#undef FLCE_RA
-#undef FLCE_RB
-#undef FLCE_LA
-#undef FLCE_LB
-#undef FLCE_HALF
-#undef FLCE_NOLOAD
 }
 
 }  // namespace fast
