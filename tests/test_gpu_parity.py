@@ -26,7 +26,7 @@ TOL = {"f32": dict(loss=1e-5, grad=1e-4, lse=2e-6), "bf16": dict(loss=2e-3, grad
 def _need_gpu_and_clean_env(monkeypatch):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    for k in ("FLCE_WINDOWS", "FLCE_VC_TILES", "FLCE_NC_TILES"):
+    for k in ("FLCE_WINDOWS", "FLCE_VC_TILES", "FLCE_NC_TILES", "FLCE_GENERIC"):
         monkeypatch.delenv(k, raising=False)
     yield
 
@@ -87,16 +87,37 @@ def test_ragged_and_small_shapes(wl):
     check_against_oracle(wl, I.make_inputs(wl), grad_loss=1.0 if wl.reduction == "mean" else -0.75)
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype,generic", [("bf16", 0), ("bf16", 1), ("f32", 0)])
 @pytest.mark.parametrize("windows,vc,nc", [(1, 1, 1), (3, 2, 1), (5, 1, 2), (64, 3, 3)])
-def test_chunk_and_window_splits(monkeypatch, dtype, windows, vc, nc):
+def test_chunk_and_window_splits(monkeypatch, dtype, generic, windows, vc, nc):
     """Forces several vocabulary windows in the forward and several vocabulary / token chunks in
-    the backward on a small problem, so the merge and the fixed-order accumulation are exercised."""
+    the backward on a small problem, so the merge and the fixed-order accumulation are exercised;
+    for bf16 once with the tuned main loop (operands read in place) and once with the generic one
+    (transposed copies)."""
     monkeypatch.setenv("FLCE_WINDOWS", str(windows))
     monkeypatch.setenv("FLCE_VC_TILES", str(vc))
     monkeypatch.setenv("FLCE_NC_TILES", str(nc))
-    wl = custom(f"split_{dtype}_{windows}_{vc}_{nc}", 700, 136, 1500, dtype, 21, ignore_frac=0.05)
+    monkeypatch.setenv("FLCE_GENERIC", str(generic))
+    wl = custom(f"split_{dtype}_{generic}_{windows}_{vc}_{nc}", 700, 160, 1500, dtype, 21, ignore_frac=0.05)
     check_against_oracle(wl, I.make_inputs(wl))
+
+
+@pytest.mark.parametrize("d", [32, 96, 416])
+def test_tuned_loop_short_and_odd_k(d):
+    """K extents of 1, 3 and 13 stages of the tuned bf16 loop (prologue / drain paths), hidden size not a
+    multiple of the 256-wide output tile."""
+    wl = custom(f"bf16_k{d}", 515, d, 1027, "bf16", 23, ignore_frac=0.07)
+    check_against_oracle(wl, I.make_inputs(wl))
+
+
+def test_generic_loop_matches_tuned_loop_closely(monkeypatch):
+    wl = custom("both_loops", 520, 256, 2100, "bf16", 24, ignore_frac=0.1)
+    x = I.make_inputs(wl)
+    a = run_workload(wl, x)
+    monkeypatch.setenv("FLCE_GENERIC", "1")
+    b = run_workload(wl, x)
+    assert abs(a["loss"] - b["loss"]) <= 1e-6 * abs(a["loss"])
+    assert nerr(a["dH"], b["dH"]) < 1e-2 and nerr(a["dW"], b["dW"]) < 1e-2
 
 
 @pytest.mark.parametrize("dtype,w_std", [("bf16", 1.0), ("f32", 0.5)])
