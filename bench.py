@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--workload", default="llama3_8b")
     ap.add_argument("--oracle-rows", type=int, default=None, help="rows of the CPU baseline sample (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with events")
+    ap.add_argument("--copy-calibration", type=int, default=0,
+                    help="bytes of one plain device copy issued before the timed region (a yardstick for "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures the one-GPU kernel path only; run with --gpus 1", file=sys.stderr)
@@ -77,6 +80,12 @@ def main():
         st = s.backward()
         assert st == B.FLCE_OK, B.flce_status_string(st)
 
+    if args.copy_calibration:
+        src = torch.empty(args.copy_calibration, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -97,6 +106,10 @@ def main():
 
     ms_per_step = dt / args.steps * 1e3
     flops = 8.0 * wl.N * wl.d * wl.V
+    # what the kernels execute: the forward runs every row, the three backward contractions run the counted
+    # rows only, in whole 256-row tiles
+    rows_bwd = -(-n_valid // 256) * 256
+    flops_executed = 2.0 * wl.d * wl.V * (-(-wl.N // 256) * 256) + 6.0 * wl.d * wl.V * rows_bwd
     tflops = flops / (ms_per_step * 1e-3) / 1e12
     peak = BF16_MFMA_PEAK_TFLOPS if wl.dtype == "bf16" else F32_MFMA_PEAK_TFLOPS
 
@@ -136,7 +149,11 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "d": wl.d, "V": wl.V, "reduction": wl.reduction,
                    "targets": wl.targets, "ignore_frac": wl.ignore_frac, "seed": wl.seed},
-        "tflops_8NdV": tflops, "frac_of_mfma_peak": tflops / peak, "loss": loss, "n_valid": n_valid,
+        "tflops_8NdV": tflops, "frac_of_mfma_peak": tflops / peak,
+        "tflops_executed": flops_executed / (ms_per_step * 1e-3) / 1e12,
+        "flops_note": "8NdV counts the ignored rows too; the backward skips them (their rows of G are zero), "
+                      "so executed flops are 2NdV + 6*rows_counted*d*V",
+        "loss": loss, "n_valid": n_valid,
         "memory": {"peak_allocated_bytes": int(torch.cuda.max_memory_allocated()),
                    "path_tensor_bytes": int(s.tensor_bytes()), "workspace_bytes": int(s.ws.numel()),
                    "naive_fp32_logits_bytes": int(wl.naive_logits_bytes),

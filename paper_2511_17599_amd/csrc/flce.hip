@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
 #include <mutex>
 #include <vector>
@@ -66,8 +67,10 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   p.npad = (int64_t)p.n_rb * TILE;
 
   // Windows (Section 3.2.1): enough (row block, window) workgroups to cover the CUs.
+  // At least 4, so that the 32 workgroups resident on one XCD are 8 row blocks x 4 windows and
+  // share both operands through that XCD's L2 (one window would stream every H block from HBM).
   int win = env_int("FLCE_WINDOWS", 0, 0, 1 << 16);
-  if (win == 0) win = p.n_rb >= NUM_CU ? 1 : (int)ceil_div(NUM_CU, p.n_rb);
+  if (win == 0) win = (int)std::max<int64_t>(4, ceil_div(NUM_CU, p.n_rb));
   if (win > p.n_vt) win = p.n_vt;
   p.n_win = win;
   int64_t o = ALIGN;                                  // header
@@ -79,7 +82,7 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
 
   // Backward staging: a fixed-size G tile of at most vc x nc 256-tiles.
   const int vc_max = env_int("FLCE_VC_TILES", 64, 1, 4096);
-  const int nc_max = env_int("FLCE_NC_TILES", 32, 1, 4096);
+  const int nc_max = env_int("FLCE_NC_TILES", 64, 1, 4096);
   p.n_vch = (int)ceil_div(p.n_vt, vc_max);
   p.n_nch = (int)ceil_div(p.n_rb, nc_max);
   p.vc_tiles = (int)ceil_div(p.n_vt, p.n_vch);

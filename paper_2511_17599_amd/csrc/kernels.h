@@ -14,6 +14,8 @@
 //             contract_kernel (Eq. 4 and Eq. 5 as output-stationary MFMA
 //             contractions with a fixed chunk order; Gamma applied at the flush)
 #pragma once
+#include <type_traits>
+
 #include "mainloop_fast.h"
 #include "tile_mma.h"
 
@@ -126,41 +128,44 @@ __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
     const int v0 = vt * TILE;
     L::run(W, ld_bytes, v0, V, H, ld_bytes, n0, N, (int)ld_bytes, lds, acc);
 
-    if (v0 + TILE > V) {       // ragged last vocabulary tile: padded logits are -inf
-#pragma unroll
-      for (int i = 0; i < L::WM; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (v0 + L::tile_m(i, r) >= V) {
-#pragma unroll
-            for (int j = 0; j < L::WN; ++j) acc[i][j][r] = NEG_INF;
-          }
-    }
+    // Online update of (m, a) and the target gather, one 32 x 32 accumulator block at a time
+    // (16 logits of one token per lane).  All 32 rows of a block belong to one wavefront, so
+    // "entirely behind the vocabulary's end" and "straddles the end" are wave-uniform tests;
+    // padded rows count as logits of -inf.
 #pragma unroll
     for (int j = 0; j < L::WN; ++j) {
-      float tmax = NEG_INF;
 #pragma unroll
-      for (int i = 0; i < L::WM; ++i)
+      for (int i = 0; i < L::WM; ++i) {
+        const int blk0 = v0 + __builtin_amdgcn_readfirstlane(L::tile_m(i, 0) & ~31);   // first row of the block
+        if (blk0 >= V) continue;
+        float z[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, acc[i][j][r]);
-      const float mn = fmaxf(m[j], tmax);
-      const float ms = (mn == NEG_INF) ? 0.f : mn;     // all-padded slice: keep exp arguments finite
-      float sum = 0.f;
-#pragma unroll
-      for (int i = 0; i < L::WM; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum += fast_exp2((acc[i][j][r] - ms) * LOG2E);
-      a[j] = a[j] * fast_exp2((m[j] - ms) * LOG2E) + sum;
-      m[j] = mn;
-
-      const int rel = tgt[j] - v0;
-      const bool mine = (unsigned)rel < (unsigned)TILE && tgt[j] >= 0;
-      if (__ballot(mine) != 0ull) {
-#pragma unroll
-        for (int i = 0; i < L::WM; ++i)
+        for (int r = 0; r < 16; ++r) z[r] = acc[i][j][r];
+        if (blk0 + 32 > V) {
 #pragma unroll
           for (int r = 0; r < 16; ++r)
-            if (mine && L::tile_m(i, r) == rel) zt[j] = acc[i][j][r];
+            if (v0 + L::tile_m(i, r) >= V) z[r] = NEG_INF;
+        }
+        float bmax = z[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) bmax = fmaxf(bmax, z[r]);
+        const float mn = fmaxf(m[j], bmax);
+        const float ms = (mn == NEG_INF) ? 0.f : mn;     // nothing but padding so far: keep exp arguments finite
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += fast_exp2((z[r] - ms) * LOG2E);
+        a[j] = a[j] * fast_exp2((m[j] - ms) * LOG2E) + sum;
+        m[j] = mn;
+
+        const int rel = tgt[j] - blk0;                    // target row inside this block, if any
+        const bool mine = (unsigned)rel < 32u && tgt[j] >= 0;
+        if (__ballot(mine) != 0ull) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (mine && (L::tile_m(i, r) & 31) == rel) zt[j] = z[r];
+        }
+        // one block at a time in VGPRs
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
@@ -453,6 +458,7 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(
 #pragma unroll
           for (int e = 0; e < 4; ++e) GT[(int64_t)(vl + e) * ldGT + nl] = Pack4<T>::one(g[e]);
         }
+        if (rq == 3) __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
       }
   }
 }
@@ -533,6 +539,7 @@ __global__ __launch_bounds__(L::THREADS) void contract_kernel(
           Pack4<T>::store(out + orow * d + m, v[0] * scale + 0.f, v[1] * scale + 0.f, v[2] * scale + 0.f,
                           v[3] * scale + 0.f);
         }
+        if (rq == 3) __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
       }
   }
 }
