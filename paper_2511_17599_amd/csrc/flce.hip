@@ -37,11 +37,12 @@ struct Plan {
   int64_t npad;
   // forward
   int n_win;
-  int64_t off_part, off_blk_loss, off_blk_cnt, off_blk_oor, fwd_bytes;
+  int64_t off_part, off_blk_loss, off_blk_cnt, off_blk_oor, off_fHT, fwd_bytes;
   // backward
   int n_vch, n_nch;        // chunks along vocabulary / tokens
   int vc_tiles, nc_tiles;  // largest chunk, in tiles
-  bool fast;               // tuned bf16 loop: no transposed copies
+  bool fast;               // tuned bf16 loop: W, Hc and G read in place by the contractions
+  bool hkr;                // forward / recompute read a transposed copy of H (needs its window below 2^31 bytes)
   int64_t off_Hc, off_rowmap, off_tgt, off_lsec, off_HT, off_WT, off_G, off_GT, off_dHacc, off_dWacc, bwd_bytes;
 };
 
@@ -78,7 +79,8 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   p.off_blk_loss = o;   o = align_up(o + (int64_t)p.n_rb * 4, ALIGN);
   p.off_blk_cnt = o;    o = align_up(o + (int64_t)p.n_rb * 4, ALIGN);
   p.off_blk_oor = o;    o = align_up(o + (int64_t)p.n_rb * 4, ALIGN);
-  p.fwd_bytes = o;
+  p.off_fHT = o;        // sized below, once the loop flavour is known
+  const int64_t fwd_fixed = o;
 
   // Backward staging: a fixed-size G tile of at most vc x nc 256-tiles.
   const int vc_max = env_int("FLCE_VC_TILES", 64, 1, 4096);
@@ -89,6 +91,8 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   p.nc_tiles = (int)ceil_div(p.n_rb, p.n_nch);
   const int64_t vc_pad = (int64_t)p.vc_tiles * TILE, nc_pad = (int64_t)p.nc_tiles * TILE;
   p.fast = fast_loop_ok(p);
+  p.hkr = p.fast && (d + 32) * p.npad * 2 < ((int64_t)1 << 31);
+  p.fwd_bytes = fwd_fixed + (p.hkr ? align_up(d * p.npad * p.esize, ALIGN) : 0);
   o = ALIGN;
   p.off_Hc = o;     o = align_up(o + d * p.npad * p.esize, ALIGN);
   p.off_rowmap = o; o = align_up(o + p.npad * 4, ALIGN);
@@ -96,7 +100,7 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   p.off_lsec = o;   o = align_up(o + p.npad * 4, ALIGN);
   p.off_G = o;      o = align_up(o + nc_pad * vc_pad * p.esize, ALIGN);
   // K-contiguous copies, only for main loops that cannot read an operand across memory rows
-  p.off_HT = o;     if (!p.fast) o = align_up(o + d * p.npad * p.esize, ALIGN);
+  p.off_HT = o;     if (!p.fast || p.hkr) o = align_up(o + d * p.npad * p.esize, ALIGN);
   p.off_WT = o;     if (!p.fast) o = align_up(o + d * vc_pad * p.esize, ALIGN);
   p.off_GT = o;     if (!p.fast) o = align_up(o + nc_pad * vc_pad * p.esize, ALIGN);
   p.off_dHacc = o;  if (p.n_vch > 1) o = align_up(o + N * d * 4, ALIGN);
@@ -144,8 +148,12 @@ hipError_t allow_big_lds(K kernel, int bytes) {
 template <typename T, typename L>
 hipError_t prepare_kernels() {
   hipError_t e;
-  if ((e = allow_big_lds(fwd_tiles_kernel<T, L>, L::LDS)) != hipSuccess) return e;
-  if ((e = allow_big_lds(recompute_kernel<T, L>, L::LDS)) != hipSuccess) return e;
+  if ((e = allow_big_lds(fwd_tiles_kernel<T, L, false>, L::LDS)) != hipSuccess) return e;
+  if ((e = allow_big_lds(recompute_kernel<T, L, false>, L::LDS)) != hipSuccess) return e;
+  if constexpr (L::TRANSPOSING) {
+    if ((e = allow_big_lds(fwd_tiles_kernel<T, L, true>, L::LDS)) != hipSuccess) return e;
+    if ((e = allow_big_lds(recompute_kernel<T, L, true>, L::LDS)) != hipSuccess) return e;
+  }
   if constexpr (L::TRANSPOSING) {
     if ((e = allow_big_lds(contract_kernel<T, L, OPS_DH_TR>, L::LDS)) != hipSuccess) return e;
     if ((e = allow_big_lds(contract_kernel<T, L, OPS_DW_TR>, L::LDS)) != hipSuccess) return e;
@@ -155,7 +163,7 @@ hipError_t prepare_kernels() {
   return hipSuccess;
 }
 
-template <typename T, typename L>
+template <typename T, typename U, typename L>
 flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t* y, int64_t ignore_index,
                       int mean, float* loss_out, float* lse_out, char* ws, hipStream_t st) {
   if (prepare_kernels<T, L>() != hipSuccess) return FLCE_ERR_HIP;
@@ -165,11 +173,27 @@ flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t
   int* blk_cnt = reinterpret_cast<int*>(ws + p.off_blk_cnt);
   int* blk_oor = reinterpret_cast<int*>(ws + p.off_blk_oor);
   const int grid = p.n_rb * p.n_win;
-  {
+  bool hkr = false;
+  if constexpr (L::TRANSPOSING) hkr = p.hkr;
+  if (hkr) {
+    if constexpr (L::TRANSPOSING) {
+      T* HT = reinterpret_cast<T*>(ws + p.off_fHT);
+      {
+        // H^T [d][npad], zero padded: the forward's second operand, read across memory rows
+        ProfScope ps(FLCE_PROF_FWD_EPILOGUE, st);
+        transpose_pad_kernel<U><<<dim3((unsigned)ceil_div(p.npad, 64), (unsigned)ceil_div(p.d, 64)), 256, 0, st>>>(
+            static_cast<const U*>(H), p.d, (int)p.N, 0, (int)p.d, reinterpret_cast<U*>(HT), p.npad, (int)p.npad);
+      }
+      ProfScope ps(FLCE_PROF_FWD_TILES, st);
+      fwd_tiles_kernel<T, L, true><<<grid, L::THREADS, L::LDS, st>>>(
+          static_cast<const T*>(H), HT, static_cast<const T*>(W), y, (int)p.N, (int)p.d, (int)p.V, ignore_index,
+          p.n_rb, p.n_win, p.n_vt, part);
+    }
+  } else {
     ProfScope ps(FLCE_PROF_FWD_TILES, st);
-    fwd_tiles_kernel<T, L><<<grid, L::THREADS, L::LDS, st>>>(static_cast<const T*>(H), static_cast<const T*>(W), y,
-                                                          (int)p.N, (int)p.d, (int)p.V, ignore_index, p.n_rb,
-                                                          p.n_win, p.n_vt, part);
+    fwd_tiles_kernel<T, L, false><<<grid, L::THREADS, L::LDS, st>>>(
+        static_cast<const T*>(H), nullptr, static_cast<const T*>(W), y, (int)p.N, (int)p.d, (int)p.V, ignore_index,
+        p.n_rb, p.n_win, p.n_vt, part);
   }
   {
     ProfScope ps(FLCE_PROF_FWD_EPILOGUE, st);
@@ -208,8 +232,9 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     gather_rows_kernel<<<npad, 256, 0, st>>>(static_cast<const char*>(H), row_bytes, rowmap, lse,
                                              reinterpret_cast<char*>(Hc), lse_c);
     zero_uncounted_rows_kernel<<<N, 256, 0, st>>>(y, V, ignore_index, static_cast<char*>(dH), row_bytes);
-    if constexpr (!L::TRANSPOSING) {
-      // Hc^T [d][npad]: K-contiguous operand of the dW contraction
+    if (!L::TRANSPOSING || p.hkr) {
+      // Hc^T [d][npad]: the dW contraction's K-contiguous operand (generic loop), or the recompute's
+      // operand read across memory rows (tuned loop)
       transpose_pad_kernel<U><<<dim3((unsigned)ceil_div(p.npad, 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
           reinterpret_cast<const U*>(Hc), d, npad, 0, d, reinterpret_cast<U*>(HT), p.npad, npad);
     }
@@ -229,9 +254,18 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
       const int n_nt = nt1 - nt0;
       {
         ProfScope ps(FLCE_PROF_RECOMPUTE, st);
-        recompute_kernel<T, L><<<n_nt * n_vt, L::THREADS, L::LDS, st>>>(Hc, static_cast<const T*>(W), tgt_c, lse_c, hdr,
-                                                                        npad, d, V, nt0, n_nt, vt0, n_vt, G, vc_pad,
-                                                                        GT, nc_pad);
+        bool hkr = false;
+        if constexpr (L::TRANSPOSING) hkr = p.hkr;
+        if (hkr) {
+          if constexpr (L::TRANSPOSING)
+            recompute_kernel<T, L, true><<<n_nt * n_vt, L::THREADS, L::LDS, st>>>(
+                Hc, HT, static_cast<const T*>(W), tgt_c, lse_c, hdr, npad, d, V, nt0, n_nt, vt0, n_vt, G, vc_pad, GT,
+                nc_pad);
+        } else {
+          recompute_kernel<T, L, false><<<n_nt * n_vt, L::THREADS, L::LDS, st>>>(
+              Hc, nullptr, static_cast<const T*>(W), tgt_c, lse_c, hdr, npad, d, V, nt0, n_nt, vt0, n_vt, G, vc_pad,
+              GT, nc_pad);
+        }
       }
       // dW[vocab chunk] += GT . Hc^T[:, row chunk]^T   (contraction over the compact rows of the chunk)
       {
@@ -313,13 +347,13 @@ flce_status flce_forward(const void* H, const void* W, const int64_t* targets, i
   char* ws = static_cast<char*>(workspace);
   if (dt == FLCE_DTYPE_BF16) {
     if (p.fast)
-      return flce::forward_t<flce::bf16_t, flce::FastLoop>(p, H, W, targets, ignore_index, mean, loss_out, lse_out,
-                                                           ws, st);
-    return flce::forward_t<flce::bf16_t, flce::GenericLoop<flce::bf16_t>>(p, H, W, targets, ignore_index, mean,
-                                                                          loss_out, lse_out, ws, st);
+      return flce::forward_t<flce::bf16_t, uint16_t, flce::FastLoop>(p, H, W, targets, ignore_index, mean, loss_out,
+                                                                     lse_out, ws, st);
+    return flce::forward_t<flce::bf16_t, uint16_t, flce::GenericLoop<flce::bf16_t>>(p, H, W, targets, ignore_index,
+                                                                                    mean, loss_out, lse_out, ws, st);
   }
-  return flce::forward_t<float, flce::GenericLoop<float>>(p, H, W, targets, ignore_index, mean, loss_out, lse_out, ws,
-                                                          st);
+  return flce::forward_t<float, uint32_t, flce::GenericLoop<float>>(p, H, W, targets, ignore_index, mean, loss_out,
+                                                                    lse_out, ws, st);
 }
 
 flce_status flce_backward(const void* H, const void* W, const int64_t* targets, const float* lse, int64_t N,

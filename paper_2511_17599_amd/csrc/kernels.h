@@ -57,6 +57,15 @@ struct FastLoop {         // bf16, K a multiple of 32 elements; 4 wavefronts 2 x
     const fast::Operand Bs{static_cast<const char*>(B), ldb_bytes, b_row0, b_rows, 0};
     fast::mainloop<fast::KC, fast::KC>(As, Bs, k_bytes / 2, lds, acc);
   }
+  // Same contraction with B given transposed: BT[k][n] (K over memory rows, ldbt_bytes per row),
+  // tile columns b_col0 .. b_col0 + 255, all inside the padded row.
+  static __device__ __forceinline__ void run_bt(const void* A, int64_t lda_bytes, int a_row0, int a_rows,
+                                                const void* BT, int64_t ldbt_bytes, int b_col0, int k_elems,
+                                                char* lds, f32x16 (&acc)[WM][WN]) {
+    const fast::Operand As{static_cast<const char*>(A), lda_bytes, a_row0, a_rows, 0};
+    const fast::Operand Bs{static_cast<const char*>(BT) + (int64_t)b_col0 * 2, ldbt_bytes, 0, k_elems, TILE * 2};
+    fast::mainloop<fast::KC, fast::KR>(As, Bs, k_elems, lds, acc);
+  }
 };
 
 constexpr float LOG2E = 1.4426950408889634f;
@@ -100,9 +109,12 @@ __device__ __forceinline__ void merge_fixed(const float (&m)[S], const float (&a
 // (m, a, z_target) in registers across the vocabulary tiles of its window.
 // part = [3][n_win][n_rb * 256] floats: m, a, z_target per (window, row).
 // ------------------------------------------------------------------------------------
-template <typename T, typename L>
+// HKR: the hidden states are also given transposed, HT[d][n_rb * 256] (zero padded), and the main
+// loop reads that copy (an operand whose K index runs over memory rows is fetched in 512-byte
+// runs and measures faster than two K-contiguous operands).
+template <typename T, typename L, bool HKR>
 __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
-    const T* __restrict__ H, const T* __restrict__ W, const int64_t* __restrict__ y,
+    const T* __restrict__ H, const T* __restrict__ HT, const T* __restrict__ W, const int64_t* __restrict__ y,
     int N, int d, int V, int64_t ignore_index, int n_rb, int n_win, int n_vt, float* __restrict__ part) {
   extern __shared__ __align__(16) char lds[];
   const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
@@ -126,7 +138,8 @@ __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
   f32x16 acc[L::WM][L::WN];
   for (int vt = vt_begin; vt < vt_end; ++vt) {
     const int v0 = vt * TILE;
-    L::run(W, ld_bytes, v0, V, H, ld_bytes, n0, N, (int)ld_bytes, lds, acc);
+    if constexpr (HKR) L::run_bt(W, ld_bytes, v0, V, HT, (int64_t)n_rb * TILE * sizeof(T), n0, d, lds, acc);
+    else L::run(W, ld_bytes, v0, V, H, ld_bytes, n0, N, (int)ld_bytes, lds, acc);
 
     // Online update of (m, a) and the target gather, one 32 x 32 accumulator block at a time
     // (16 logits of one token per lane).  All 32 rows of a block belong to one wavefront, so
@@ -418,9 +431,9 @@ template <> struct Pack4<bf16_t> {
 // Tiles that lie entirely behind the last counted row return at once; the
 // contractions never read them.
 // ------------------------------------------------------------------------------------
-template <typename T, typename L>
+template <typename T, typename L, bool HKR>
 __global__ __launch_bounds__(L::THREADS) void recompute_kernel(
-    const T* __restrict__ Hc, const T* __restrict__ W, const int* __restrict__ tgt_c,
+    const T* __restrict__ Hc, const T* __restrict__ HcT, const T* __restrict__ W, const int* __restrict__ tgt_c,
     const float* __restrict__ lse_c, const Header* __restrict__ hdr, int npad, int d, int V, int nt0, int n_nt,
     int vt0, int n_vt, T* __restrict__ G, int64_t ldG, T* __restrict__ GT, int64_t ldGT) {
   extern __shared__ __align__(16) char lds[];
@@ -431,7 +444,8 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(
   if (n0 >= (int)hdr->n_valid) return;
   const int64_t ld_bytes = (int64_t)d * sizeof(T);
   f32x16 acc[L::WM][L::WN];
-  L::run(W, ld_bytes, v0, V, Hc, ld_bytes, n0, npad, (int)ld_bytes, lds, acc);
+  if constexpr (HKR) L::run_bt(W, ld_bytes, v0, V, HcT, (int64_t)npad * sizeof(T), n0, d, lds, acc);
+  else L::run(W, ld_bytes, v0, V, Hc, ld_bytes, n0, npad, (int)ld_bytes, lds, acc);
 
 #pragma unroll
   for (int j = 0; j < L::WN; ++j) {

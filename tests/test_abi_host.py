@@ -41,7 +41,7 @@ def test_workspace_has_no_NV_term():
     ws = B.flce_workspace_bytes(131072, 4096, 128256, B.FLCE_DTYPE_BF16, 1)
     assert ws < 0.1 * 131072 * 128256 * 4
     fw = B.flce_workspace_bytes(131072, 4096, 128256, B.FLCE_DTYPE_BF16, 0)
-    assert fw < 64 * (1 << 20)
+    assert fw < 131072 * 4096 * 2 + 64 * (1 << 20)          # at most one copy of H plus per-row partials
 
 
 @pytest.mark.parametrize("N,d,V", [(0, 64, 64), (64, 0, 64), (64, 64, 0), (64, 60, 64), (-1, 64, 64)])
