@@ -83,8 +83,8 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   const int64_t fwd_fixed = o;
 
   // Backward staging: a fixed-size G tile of at most vc x nc 256-tiles.
-  const int vc_max = env_int("FLCE_VC_TILES", 64, 1, 4096);
-  const int nc_max = env_int("FLCE_NC_TILES", 64, 1, 4096);
+  const int vc_max = env_int("FLCE_VC_TILES", 128, 1, 4096);
+  const int nc_max = env_int("FLCE_NC_TILES", 32, 1, 4096);
   p.n_vch = (int)ceil_div(p.n_vt, vc_max);
   p.n_nch = (int)ceil_div(p.n_rb, nc_max);
   p.vc_tiles = (int)ceil_div(p.n_vt, p.n_vch);

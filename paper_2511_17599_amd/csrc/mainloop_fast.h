@@ -194,100 +194,119 @@ __device__ __forceinline__ void read_frag(bf16x8 (&f)[4], const FragAddr<LAYOUT>
   }
 }
 
-// acc = A_tile . B_tile^T over k_elems of K (a multiple of 32).  On return all wavefronts
-// have passed a barrier after their last LDS read, so the caller may reuse `lds`.
+// The contraction of one tile, split in two calls so that a kernel that works on several
+// tiles can request the first stages of the next tile before it post-processes the
+// accumulators of the current one:
+//   start(A, B, k_elems, lds): requests K tiles 0..2 into stages 0..2 (all stages must be free:
+//                              every wavefront has passed the final barrier of the previous run);
+//   run(lds, acc):             acc = A_tile . B_tile^T over k_elems of K (a multiple of 32).  On
+//                              return all wavefronts have passed a barrier after their last LDS
+//                              read, so the caller may reuse `lds` or call start() again.
+template <int LA, int LB>
+struct Pipe {
+  Loader<LA> la;
+  Loader<LB> lb;
+  FragAddr<LA> fa;
+  FragAddr<LB> fb;
+  int KT, lds_wave;
+
+  __device__ __forceinline__ void start(const Operand& A, const Operand& B, int k_elems, char* lds) {
+    KT = k_elems / BK;
+    la.init(A, k_elems);
+    lb.init(B, k_elems);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    fa.init(wave >> 1);
+    fb.init(wave & 1);
+    lds_wave = wave * 4096;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+      if (s < KT) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) la.issue(i, lds + s * STAGE + lds_wave, s);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) lb.issue(i, lds + s * STAGE + OPER + lds_wave, s);
+      }
+  }
+
+  __device__ __forceinline__ void run(char* lds, f32x16 (&acc)[WM][WN]) {
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    constexpr int RA = FragAddr<LA>::READS, RB = FragAddr<LB>::READS, RT = RA + RB;
+
+    // tile 0 has landed once at most tiles 1 and 2 are in flight
+    if (KT > 2) wait_vm_and_lds<2 * LOADS_PER_TILE>();
+    else if (KT > 1) wait_vm_and_lds<LOADS_PER_TILE>();
+    else wait_vm_and_lds<0>();
+    __builtin_amdgcn_s_barrier();
+    Frags f0, f1;
+#pragma unroll
+    for (int t = 0; t < RA; ++t) read_frag<LA>(f0.a, fa, lds, 0, t);
+#pragma unroll
+    for (int t = 0; t < RB; ++t) read_frag<LB>(f0.b, fb, lds + OPER, 0, t);
+
+    // One half of a K step: the 16 MFMAs of fragment set FM; between them the LDS reads that
+    // fill fragment set FR (stage `st`, MFMA K step ks) and, if load_kt >= 0, the 4 global
+    // requests of operand `which` (0 = A, 1 = B) of K tile load_kt into stage `lst`.
+    auto half_step = [&](const Frags& FM, Frags& FR, const char* st, int ks, int which, int load_kt, char* lst) {
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int s = 0; s < 16; ++s) {
+        acc[s >> 2][s & 3] =
+            __builtin_amdgcn_mfma_f32_32x32x16_bf16(FM.a[s >> 2], FM.b[s & 3], acc[s >> 2][s & 3], 0, 0, 0);
+        // reads t with t * 16 / RT == s: spread evenly over the 16 slots
+#pragma unroll
+        for (int t = 0; t < RT; ++t)
+          if (t * 16 / RT == s) {
+            if (t < RA) read_frag<LA>(FR.a, fa, st, ks, t);
+            else read_frag<LB>(FR.b, fb, st + OPER, ks, t - RA);
+          }
+        if ((s & 3) == 2 && load_kt >= 0) {
+          if (which == 0) la.issue(s >> 2, lst + lds_wave, load_kt);
+          else lb.issue(s >> 2, lst + OPER + lds_wave, load_kt);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+
+    // Steady state: K step kt computes tile kt and requests tile kt+3 into the stage that
+    // was freed by the barrier of step kt-1.
+    int kt = 0;
+    for (; kt + NS - 1 < KT; ++kt) {
+      const char* cur = lds + (kt & (NS - 1)) * STAGE;
+      const char* nxt = lds + ((kt + 1) & (NS - 1)) * STAGE;
+      char* lst = lds + ((kt + NS - 1) & (NS - 1)) * STAGE;
+      half_step(f0, f1, cur, 1, 0, kt + NS - 1, lst);
+      // tile kt+1 has landed once only tile kt+2 and the first half of tile kt+3 are in flight;
+      // lgkmcnt(0): this wavefront holds all its fragments of tile kt
+      wait_vm_and_lds<LOADS_PER_TILE + LOADS_PER_TILE / 2>();
+      __builtin_amdgcn_s_barrier();
+      half_step(f1, f0, nxt, 0, 1, kt + NS - 1, lst);
+    }
+    // Drain: the last (up to NS-1) tiles, nothing left to request.
+    for (; kt < KT; ++kt) {
+      const char* cur = lds + (kt & (NS - 1)) * STAGE;
+      const char* nxt = lds + ((kt + 1) & (NS - 1)) * STAGE;   // past the last tile: stale data, never used
+      half_step(f0, f1, cur, 1, 0, -1, nullptr);
+      if (kt + 2 < KT) wait_vm_and_lds<LOADS_PER_TILE>();
+      else wait_vm_and_lds<0>();
+      __builtin_amdgcn_s_barrier();
+      half_step(f1, f0, nxt, 0, 1, -1, nullptr);
+    }
+    wait_vm_and_lds<0>();
+    __builtin_amdgcn_s_barrier();
+  }
+};
+
 template <int LA, int LB>
 __device__ __forceinline__ void mainloop(const Operand& A, const Operand& B, int k_elems, char* lds,
                                          f32x16 (&acc)[WM][WN]) {
-#pragma unroll
-  for (int i = 0; i < WM; ++i)
-#pragma unroll
-    for (int j = 0; j < WN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  const int KT = k_elems / BK;
-  Loader<LA> la;
-  Loader<LB> lb;
-  la.init(A, k_elems);
-  lb.init(B, k_elems);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  FragAddr<LA> fa;
-  FragAddr<LB> fb;
-  fa.init(wave >> 1);
-  fb.init(wave & 1);
-  const int lds_wave = wave * 4096;
-  constexpr int RA = FragAddr<LA>::READS, RB = FragAddr<LB>::READS, RT = RA + RB;
-
-  // prologue: tiles 0..2 requested, tile 0 landed
-#pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < KT) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) la.issue(i, lds + s * STAGE + lds_wave, s);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) lb.issue(i, lds + s * STAGE + OPER + lds_wave, s);
-    }
-  if (KT > 2) wait_vm_and_lds<2 * LOADS_PER_TILE>();
-  else if (KT > 1) wait_vm_and_lds<LOADS_PER_TILE>();
-  else wait_vm_and_lds<0>();
-  __builtin_amdgcn_s_barrier();
-  Frags f0, f1;
-#pragma unroll
-  for (int t = 0; t < RA; ++t) read_frag<LA>(f0.a, fa, lds, 0, t);
-#pragma unroll
-  for (int t = 0; t < RB; ++t) read_frag<LB>(f0.b, fb, lds + OPER, 0, t);
-
-  // One half of a K step: the 16 MFMAs of fragment set FM; between them the LDS reads that
-  // fill fragment set FR (stage `st`, MFMA K step ks) and, if load_kt >= 0, the 4 global
-  // requests of operand `which` (0 = A, 1 = B) of K tile load_kt into stage `lst`.
-  auto half_step = [&](const Frags& FM, Frags& FR, const char* st, int ks, int which, int load_kt, char* lst) {
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int s = 0; s < 16; ++s) {
-      acc[s >> 2][s & 3] =
-          __builtin_amdgcn_mfma_f32_32x32x16_bf16(FM.a[s >> 2], FM.b[s & 3], acc[s >> 2][s & 3], 0, 0, 0);
-      // reads t with t * 16 / RT == s: spread evenly over the 16 slots
-#pragma unroll
-      for (int t = 0; t < RT; ++t)
-        if (t * 16 / RT == s) {
-          if (t < RA) read_frag<LA>(FR.a, fa, st, ks, t);
-          else read_frag<LB>(FR.b, fb, st + OPER, ks, t - RA);
-        }
-      if ((s & 3) == 2 && load_kt >= 0) {
-        if (which == 0) la.issue(s >> 2, lst + lds_wave, load_kt);
-        else lb.issue(s >> 2, lst + OPER + lds_wave, load_kt);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-
-  // Steady state: K step kt computes tile kt and requests tile kt+3 into the stage that
-  // was freed by the barrier of step kt-1.
-  int kt = 0;
-  for (; kt + NS - 1 < KT; ++kt) {
-    const char* cur = lds + (kt & (NS - 1)) * STAGE;
-    const char* nxt = lds + ((kt + 1) & (NS - 1)) * STAGE;
-    char* lst = lds + ((kt + NS - 1) & (NS - 1)) * STAGE;
-    half_step(f0, f1, cur, 1, 0, kt + NS - 1, lst);
-    // tile kt+1 has landed once only tile kt+2 and the first half of tile kt+3 are in flight;
-    // lgkmcnt(0): this wavefront holds all its fragments of tile kt
-    wait_vm_and_lds<LOADS_PER_TILE + LOADS_PER_TILE / 2>();
-    __builtin_amdgcn_s_barrier();
-    half_step(f1, f0, nxt, 0, 1, kt + NS - 1, lst);
-  }
-  // Drain: the last (up to NS-1) tiles, nothing left to request.
-  for (; kt < KT; ++kt) {
-    const char* cur = lds + (kt & (NS - 1)) * STAGE;
-    const char* nxt = lds + ((kt + 1) & (NS - 1)) * STAGE;   // past the last tile: stale data, never used
-    half_step(f0, f1, cur, 1, 0, -1, nullptr);
-    if (kt + 2 < KT) wait_vm_and_lds<LOADS_PER_TILE>();
-    else wait_vm_and_lds<0>();
-    __builtin_amdgcn_s_barrier();
-    half_step(f1, f0, nxt, 0, 1, -1, nullptr);
-  }
-  wait_vm_and_lds<0>();
-  __builtin_amdgcn_s_barrier();
+  Pipe<LA, LB> pipe;
+  pipe.start(A, B, k_elems, lds);
+  pipe.run(lds, acc);
 }
 
 }  // namespace fast
