@@ -114,6 +114,7 @@ def main():
     peak = BF16_MFMA_PEAK_TFLOPS if wl.dtype == "bf16" else F32_MFMA_PEAK_TFLOPS
 
     # roofline of the dominant kernel class (largest share of the step)
+    # nominal flops of each kernel class in units of N*d*V
     class_flops = {"fwd_tiles": 2.0, "recompute": 2.0, "contract_dW": 2.0, "contract_dH": 2.0}
     kernels = {}
     for k, c in class_flops.items():

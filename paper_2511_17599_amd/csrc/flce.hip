@@ -240,9 +240,62 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     }
   }
 
+  bool hkr = false;
+  if constexpr (L::TRANSPOSING) hkr = p.hkr;
+
+  // argument blocks of the three steps of chunk (vc, nc); `Gb` is the staging buffer of that chunk
+  auto chunk_vt = [&](int vc, int& vt0, int& n_vt) {
+    vt0 = (int)((int64_t)vc * p.n_vt / p.n_vch);
+    n_vt = (int)((int64_t)(vc + 1) * p.n_vt / p.n_vch) - vt0;
+  };
+  auto chunk_nt = [&](int nc, int& nt0, int& n_nt) {
+    nt0 = (int)((int64_t)nc * p.n_rb / p.n_nch);
+    n_nt = (int)((int64_t)(nc + 1) * p.n_rb / p.n_nch) - nt0;
+  };
+  auto recompute_args = [&](int vc, int nc, T* Gb) {
+    int vt0, n_vt, nt0, n_nt;
+    chunk_vt(vc, vt0, n_vt);
+    chunk_nt(nc, nt0, n_nt);
+    return RecomputeArgs<T>{Hc, HT, static_cast<const T*>(W), tgt_c, lse_c, hdr, npad, d, V, nt0, n_nt, vt0, n_vt,
+                            Gb, vc_pad, GT, nc_pad};
+  };
+  // dW[vocab chunk] += G^T . Hc[row chunk]   (contraction over the compact rows of the chunk)
+  auto dw_args = [&](int vc, int nc, const T* Gb) {
+    int vt0, n_vt, nt0, n_nt;
+    chunk_vt(vc, vt0, n_vt);
+    chunk_nt(nc, nt0, n_nt);
+    int flags = K_COMPACT;
+    if (nc > 0) flags |= READ_ACC;
+    flags |= (nc + 1 < p.n_nch) ? WRITE_ACC : WRITE_OUT;
+    if constexpr (L::TRANSPOSING)
+      return ContractArgs<T>{Hc + (int64_t)nt0 * TILE * d, d, npad - nt0 * TILE, d, Gb, vc_pad, n_nt * TILE,
+                             n_nt * TILE, nt0 * TILE, n_mt, n_vt, dWacc, vt0 * TILE, static_cast<T*>(dW), vt0 * TILE,
+                             V, flags, hdr, rowmap, grad_loss, mean};
+    else
+      return ContractArgs<T>{HT + (int64_t)nt0 * TILE, p.npad, 0, d, GT, nc_pad, n_vt * TILE, n_nt * TILE,
+                             nt0 * TILE, n_mt, n_vt, dWacc, vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags,
+                             hdr, rowmap, grad_loss, mean};
+  };
+  // dH[row chunk] += G . W[vocab chunk]      (contraction over the vocabulary chunk)
+  auto dh_args = [&](int vc, int nc, const T* Gb) {
+    int vt0, n_vt, nt0, n_nt;
+    chunk_vt(vc, vt0, n_vt);
+    chunk_nt(nc, nt0, n_nt);
+    int flags = ROWS_COMPACT;
+    if (vc > 0) flags |= READ_ACC;
+    flags |= (vc + 1 < p.n_vch) ? WRITE_ACC : WRITE_OUT;
+    if constexpr (L::TRANSPOSING)
+      return ContractArgs<T>{static_cast<const T*>(W) + (int64_t)vt0 * TILE * d, d, V - vt0 * TILE, d, Gb, vc_pad,
+                             n_nt * TILE, n_vt * TILE, 0, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH), nt0 * TILE, npad,
+                             flags, hdr, rowmap, grad_loss, mean};
+    else
+      return ContractArgs<T>{WT, vc_pad, 0, d, Gb, vc_pad, n_nt * TILE, n_vt * TILE, 0, n_mt, n_nt, dHacc, 0,
+                             static_cast<T*>(dH), nt0 * TILE, npad, flags, hdr, rowmap, grad_loss, mean};
+  };
+
   for (int vc = 0; vc < p.n_vch; ++vc) {
-    const int vt0 = (int)((int64_t)vc * p.n_vt / p.n_vch), vt1 = (int)((int64_t)(vc + 1) * p.n_vt / p.n_vch);
-    const int n_vt = vt1 - vt0;
+    int vt0, n_vt;
+    chunk_vt(vc, vt0, n_vt);
     if constexpr (!L::TRANSPOSING) {
       // W^T chunk [d][vc_pad]: K-contiguous operand of the dH contraction
       ProfScope ps(FLCE_PROF_BWD_PREP, st);
@@ -250,53 +303,31 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
           static_cast<const U*>(W), d, V, vt0 * TILE, d, reinterpret_cast<U*>(WT), vc_pad, n_vt * TILE);
     }
     for (int nc = 0; nc < p.n_nch; ++nc) {
-      const int nt0 = (int)((int64_t)nc * p.n_rb / p.n_nch), nt1 = (int)((int64_t)(nc + 1) * p.n_rb / p.n_nch);
-      const int n_nt = nt1 - nt0;
       {
+        const RecomputeArgs<T> rc = recompute_args(vc, nc, G);
         ProfScope ps(FLCE_PROF_RECOMPUTE, st);
-        bool hkr = false;
-        if constexpr (L::TRANSPOSING) hkr = p.hkr;
         if (hkr) {
           if constexpr (L::TRANSPOSING)
-            recompute_kernel<T, L, true><<<n_nt * n_vt, L::THREADS, L::LDS, st>>>(
-                Hc, HT, static_cast<const T*>(W), tgt_c, lse_c, hdr, npad, d, V, nt0, n_nt, vt0, n_vt, G, vc_pad, GT,
-                nc_pad);
+            recompute_kernel<T, L, true><<<rc.n_nt * rc.n_vt, L::THREADS, L::LDS, st>>>(rc);
         } else {
-          recompute_kernel<T, L, false><<<n_nt * n_vt, L::THREADS, L::LDS, st>>>(
-              Hc, nullptr, static_cast<const T*>(W), tgt_c, lse_c, hdr, npad, d, V, nt0, n_nt, vt0, n_vt, G, vc_pad,
-              GT, nc_pad);
+          recompute_kernel<T, L, false><<<rc.n_nt * rc.n_vt, L::THREADS, L::LDS, st>>>(rc);
         }
       }
-      // dW[vocab chunk] += GT . Hc^T[:, row chunk]^T   (contraction over the compact rows of the chunk)
       {
-        int flags = K_COMPACT;
-        if (nc > 0) flags |= READ_ACC;
-        flags |= (nc + 1 < p.n_nch) ? WRITE_ACC : WRITE_OUT;
+        const ContractArgs<T> a = dw_args(vc, nc, G);
         ProfScope ps(FLCE_PROF_CONTRACT_DW, st);
         if constexpr (L::TRANSPOSING)
-          contract_kernel<T, L, OPS_DW_TR><<<n_vt * n_mt, L::THREADS, L::LDS, st>>>(
-              Hc + (int64_t)nt0 * TILE * d, d, npad - nt0 * TILE, d, G, vc_pad, n_nt * TILE, n_nt * TILE, nt0 * TILE,
-              n_mt, n_vt, dWacc, vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags, hdr, rowmap, grad_loss, mean);
+          contract_kernel<T, L, OPS_DW_TR><<<a.n_nt * a.n_mt, L::THREADS, L::LDS, st>>>(a);
         else
-          contract_kernel<T, L, OPS_KC><<<n_vt * n_mt, L::THREADS, L::LDS, st>>>(
-              HT + (int64_t)nt0 * TILE, p.npad, 0, d, GT, nc_pad, n_vt * TILE, n_nt * TILE, nt0 * TILE, n_mt, n_vt,
-              dWacc, vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags, hdr, rowmap, grad_loss, mean);
+          contract_kernel<T, L, OPS_KC><<<a.n_nt * a.n_mt, L::THREADS, L::LDS, st>>>(a);
       }
-      // dH[row chunk] += G . W^T[:, vocab chunk]^T     (contraction over the vocabulary chunk)
       {
-        int flags = ROWS_COMPACT;
-        if (vc > 0) flags |= READ_ACC;
-        flags |= (vc + 1 < p.n_vch) ? WRITE_ACC : WRITE_OUT;
+        const ContractArgs<T> a = dh_args(vc, nc, G);
         ProfScope ps(FLCE_PROF_CONTRACT_DH, st);
         if constexpr (L::TRANSPOSING)
-          contract_kernel<T, L, OPS_DH_TR><<<n_nt * n_mt, L::THREADS, L::LDS, st>>>(
-              static_cast<const T*>(W) + (int64_t)vt0 * TILE * d, d, V - vt0 * TILE, d, G, vc_pad, n_nt * TILE,
-              n_vt * TILE, 0, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH), nt0 * TILE, npad, flags, hdr, rowmap,
-              grad_loss, mean);
+          contract_kernel<T, L, OPS_DH_TR><<<a.n_nt * a.n_mt, L::THREADS, L::LDS, st>>>(a);
         else
-          contract_kernel<T, L, OPS_KC><<<n_nt * n_mt, L::THREADS, L::LDS, st>>>(
-              WT, vc_pad, 0, d, G, vc_pad, n_nt * TILE, n_vt * TILE, 0, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH),
-              nt0 * TILE, npad, flags, hdr, rowmap, grad_loss, mean);
+          contract_kernel<T, L, OPS_KC><<<a.n_nt * a.n_mt, L::THREADS, L::LDS, st>>>(a);
       }
     }
   }

@@ -431,17 +431,25 @@ template <> struct Pack4<bf16_t> {
 // Tiles that lie entirely behind the last counted row return at once; the
 // contractions never read them.
 // ------------------------------------------------------------------------------------
+template <typename T>
+struct RecomputeArgs {
+  const T* Hc; const T* HcT; const T* W; const int* tgt_c; const float* lse_c; const Header* hdr;
+  int npad, d, V, nt0, n_nt, vt0, n_vt;
+  T* G; int64_t ldG; T* GT; int64_t ldGT;
+};
+
+// One tile of the recompute step; `bid` of `nblocks` tiles of this launch (or of this part of a fused launch).
 template <typename T, typename L, bool HKR>
-__global__ __launch_bounds__(L::THREADS) void recompute_kernel(
-    const T* __restrict__ Hc, const T* __restrict__ HcT, const T* __restrict__ W, const int* __restrict__ tgt_c,
-    const float* __restrict__ lse_c, const Header* __restrict__ hdr, int npad, int d, int V, int nt0, int n_nt,
-    int vt0, int n_vt, T* __restrict__ G, int64_t ldG, T* __restrict__ GT, int64_t ldGT) {
-  extern __shared__ __align__(16) char lds[];
-  const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
+__device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bid, int nblocks, char* lds) {
+  const T* __restrict__ Hc = a.Hc; const T* __restrict__ HcT = a.HcT; const T* __restrict__ W = a.W;
+  const int* __restrict__ tgt_c = a.tgt_c; const float* __restrict__ lse_c = a.lse_c;
+  const int npad = a.npad, d = a.d, V = a.V;
+  T* __restrict__ G = a.G; T* __restrict__ GT = a.GT; const int64_t ldG = a.ldG, ldGT = a.ldGT;
+  const int id = xcd_contiguous_id(bid, nblocks);
   int p, q;                                    // row tile, vocabulary tile inside the chunk
-  grouped_raster(id, n_nt, n_vt, 8, p, q);
-  const int n0 = (nt0 + p) * TILE, v0 = (vt0 + q) * TILE;
-  if (n0 >= (int)hdr->n_valid) return;
+  grouped_raster(id, a.n_nt, a.n_vt, 8, p, q);
+  const int n0 = (a.nt0 + p) * TILE, v0 = (a.vt0 + q) * TILE;
+  if (n0 >= (int)a.hdr->n_valid) return;
   const int64_t ld_bytes = (int64_t)d * sizeof(T);
   f32x16 acc[L::WM][L::WN];
   if constexpr (HKR) L::run_bt(W, ld_bytes, v0, V, HcT, (int64_t)npad * sizeof(T), n0, d, lds, acc);
@@ -477,6 +485,12 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(
   }
 }
 
+template <typename T, typename L, bool HKR>
+__global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> a) {
+  extern __shared__ __align__(16) char lds[];
+  recompute_tile<T, L, HKR>(a, blockIdx.x, gridDim.x, lds);
+}
+
 // ------------------------------------------------------------------------------------
 // Backward, step 2: out[n][m] (+)= sum_k A[m][k] * B[n][k]
 //   dH: A = W^T chunk [d][Vc], B = G  [rows][Vc]   (contraction over the vocabulary chunk)
@@ -497,16 +511,28 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(
 enum : int { READ_ACC = 1, WRITE_ACC = 2, WRITE_OUT = 4, ROWS_COMPACT = 8, K_COMPACT = 16 };
 enum : int { OPS_KC = 0, OPS_DH_TR = 1, OPS_DW_TR = 2 };
 
+template <typename T>
+struct ContractArgs {
+  const T* A; int64_t lda; int a_krows, d;
+  const T* B; int64_t ldb; int b_rows, k_elems, k_start, n_mt, n_nt;
+  float* accbuf; int acc_row0;
+  T* out; int out_row0, out_rows, flags;
+  const Header* hdr; const int* rowmap; float grad_loss; int mean;
+};
+
 template <typename T, typename L, int OPS>
-__global__ __launch_bounds__(L::THREADS) void contract_kernel(
-    const T* __restrict__ A, int64_t lda, int a_krows, int d, const T* __restrict__ B, int64_t ldb, int b_rows,
-    int k_elems, int k_start, int n_mt, int n_nt, float* __restrict__ accbuf, int acc_row0, T* __restrict__ out, int out_row0,
-    int out_rows, int flags, const Header* __restrict__ hdr, const int* __restrict__ rowmap, float grad_loss,
-    int mean) {
-  extern __shared__ __align__(16) char lds[];
-  const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
+__device__ __forceinline__ void contract_tile(const ContractArgs<T>& a, int bid, int nblocks, char* lds) {
+  const T* __restrict__ A = a.A; const T* __restrict__ B = a.B;
+  const int64_t lda = a.lda, ldb = a.ldb;
+  const int a_krows = a.a_krows, d = a.d, b_rows = a.b_rows, k_start = a.k_start, acc_row0 = a.acc_row0;
+  const int out_row0 = a.out_row0, out_rows = a.out_rows, flags = a.flags, mean = a.mean;
+  int k_elems = a.k_elems;
+  float* __restrict__ accbuf = a.accbuf; T* __restrict__ out = a.out;
+  const Header* __restrict__ hdr = a.hdr; const int* __restrict__ rowmap = a.rowmap;
+  const float grad_loss = a.grad_loss;
+  const int id = xcd_contiguous_id(bid, nblocks);
   int p, q;                                    // output-row tile, hidden tile
-  grouped_raster(id, n_nt, n_mt, 8, p, q);
+  grouped_raster(id, a.n_nt, a.n_mt, 8, p, q);
   const int nv = (int)hdr->n_valid;
   if ((flags & ROWS_COMPACT) && out_row0 + p * TILE >= nv) return;
   if (flags & K_COMPACT) k_elems = max(0, min(k_elems, (nv - k_start + TILE - 1) / TILE * TILE));
@@ -556,6 +582,12 @@ __global__ __launch_bounds__(L::THREADS) void contract_kernel(
         if (rq == 3) __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
       }
   }
+}
+
+template <typename T, typename L, int OPS>
+__global__ __launch_bounds__(L::THREADS) void contract_kernel(ContractArgs<T> a) {
+  extern __shared__ __align__(16) char lds[];
+  contract_tile<T, L, OPS>(a, blockIdx.x, gridDim.x, lds);
 }
 
 }  // namespace flce
