@@ -22,6 +22,14 @@ if ROOT not in sys.path:
 BF16_MFMA_PEAK_TFLOPS = 2516.6      # MI355X dense bf16: 256 CU x 4096 flop/clk x 2.4 GHz
 F32_MFMA_PEAK_TFLOPS = 157.3
 
+# HBM-side traffic per launch (bytes), from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this script scaled by the
+# same counters' reading for a plain 1 GiB copy (profiles/llama3_8b_pmc.txt); only for the default launch
+# configuration of the workload they were taken on, otherwise null.
+MEASURED_TRAFFIC = {
+    "llama3_8b": {"fwd_tiles": 14.278e9 + 0.568e9, "recompute": 3.117e9 + 0.477e9,
+                  "contract_dW": 3.402e9 + 0.323e9, "contract_dH": 3.051e9 + 0.116e9},
+}
+
 
 def cpu_baseline(wl, x, rows):
     """The oracle as it stands, on the first `rows` rows of the workload (all of W)."""
@@ -130,7 +138,9 @@ def main():
         dom = max(class_flops, key=lambda k: kernels.get(k, {}).get("ms_per_step", 0.0))
         a = kernels[dom]["tflops"]
         roofline = {"bound": "mfma", "kernel": dom, "achieved": a, "peak": peak, "unit": "TFLOP/s", "frac": a / peak,
-                    "traffic": None,
+                    "traffic": (MEASURED_TRAFFIC.get(wl.name, {}).get(dom)
+                                if not any(os.environ.get(k) for k in ("FLCE_VC_TILES", "FLCE_NC_TILES", "FLCE_WINDOWS",
+                                                                       "FLCE_GENERIC")) else None),
                     "flops_per_launch": class_flops[dom] * wl.N * wl.d * wl.V / kernels[dom]["launches_per_step"],
                     "avg_launch_ms": kernels[dom]["ms_per_step"] / kernels[dom]["launches_per_step"]}
 
