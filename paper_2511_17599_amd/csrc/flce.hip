@@ -43,7 +43,8 @@ struct Plan {
   int vc_tiles, nc_tiles;  // largest chunk, in tiles
   bool fast;               // tuned bf16 loop: W, Hc and G read in place by the contractions
   bool hkr;                // forward / recompute read a transposed copy of H (needs its window below 2^31 bytes)
-  int64_t off_Hc, off_rowmap, off_tgt, off_lsec, off_HT, off_WT, off_G, off_GT, off_dHacc, off_dWacc, bwd_bytes;
+  int split_dh, split_dw;  // K slices of the dH / dW contraction launches (1 = unsplit)
+  int64_t off_Hc, off_rowmap, off_tgt, off_lsec, off_HT, off_WT, off_G, off_GT, off_dHacc, off_dWacc, off_partial, bwd_bytes;
 };
 
 // The tuned bf16 loop needs K extents that are multiples of 32 elements and every tile's
@@ -105,6 +106,36 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   p.off_GT = o;     if (!p.fast) o = align_up(o + nc_pad * vc_pad * p.esize, ALIGN);
   p.off_dHacc = o;  if (p.n_vch > 1) o = align_up(o + N * d * 4, ALIGN);
   p.off_dWacc = o;  if (p.n_nch > 1) o = align_up(o + vc_pad * d * 4, ALIGN);
+  // Split-K for launches with too few output tiles to occupy the CUs (small N or small d): the K
+  // extent is cut into slices whose fp32 tiles are summed in slice order by a second kernel.
+  const int64_t n_mt = ceil_div(d, TILE);
+  auto auto_split = [&](int64_t tiles, int64_t k_tiles) -> int {
+    // How full the rounds of workgroups are, discounted for the partial-sum traffic of each extra
+    // slice (about 30 % of a tile's time when K is 16 tiles, less in proportion for longer K); a
+    // split has to win by 5 %.
+    int best = 1;
+    double best_score = 0.0;
+    for (int sp = 1; sp <= 8 && (sp == 1 || k_tiles / sp >= 4); ++sp) {
+      const int64_t wg = tiles * sp;
+      const double fill = (double)wg / (double)(ceil_div(wg, NUM_CU) * NUM_CU);
+      const double score = fill / (1.0 + (4.8 / (double)k_tiles) * (sp - 1));
+      if (score > best_score * (sp == 1 ? 1.0 : 1.05)) { best_score = score; best = sp; }
+    }
+    return best;
+  };
+  p.split_dh = env_int("FLCE_SPLITK_DH", 0, 0, 16);
+  p.split_dw = env_int("FLCE_SPLITK_DW", 0, 0, 16);
+  if (p.split_dh == 0) p.split_dh = auto_split(p.nc_tiles * n_mt, p.vc_tiles);
+  if (p.split_dw == 0) p.split_dw = auto_split(p.vc_tiles * n_mt, p.nc_tiles);
+  p.split_dh = (int)std::min<int64_t>(p.split_dh, p.vc_tiles);
+  p.split_dw = (int)std::min<int64_t>(p.split_dw, p.nc_tiles);
+  p.off_partial = o;
+  {
+    int64_t bytes = 0;
+    if (p.split_dh > 1) bytes = std::max(bytes, (int64_t)p.split_dh * nc_pad * d * 4);
+    if (p.split_dw > 1) bytes = std::max(bytes, (int64_t)p.split_dw * vc_pad * d * 4);
+    o = align_up(o + bytes, ALIGN);
+  }
   p.bwd_bytes = o;
   return true;
 }
@@ -243,6 +274,9 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
   bool hkr = false;
   if constexpr (L::TRANSPOSING) hkr = p.hkr;
 
+  float* partial = reinterpret_cast<float*>(ws + p.off_partial);
+  // K elements per split-K slice: whole 256-element tiles
+  auto slice_len = [](int k_elems, int n_split) { return (int)ceil_div(ceil_div(k_elems, TILE), n_split) * TILE; };
   // argument blocks of the three steps of chunk (vc, nc); `Gb` is the staging buffer of that chunk
   auto chunk_vt = [&](int vc, int& vt0, int& n_vt) {
     vt0 = (int)((int64_t)vc * p.n_vt / p.n_vch);
@@ -270,11 +304,13 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     if constexpr (L::TRANSPOSING)
       return ContractArgs<T>{Hc + (int64_t)nt0 * TILE * d, d, npad - nt0 * TILE, d, Gb, vc_pad, n_nt * TILE,
                              n_nt * TILE, nt0 * TILE, n_mt, n_vt, dWacc, vt0 * TILE, static_cast<T*>(dW), vt0 * TILE,
-                             V, flags, hdr, rowmap, grad_loss, mean};
+                             V, flags, hdr, rowmap, grad_loss, mean, p.split_dw,
+                             slice_len(n_nt * TILE, p.split_dw), partial, vc_pad * d};
     else
       return ContractArgs<T>{HT + (int64_t)nt0 * TILE, p.npad, 0, d, GT, nc_pad, n_vt * TILE, n_nt * TILE,
                              nt0 * TILE, n_mt, n_vt, dWacc, vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags,
-                             hdr, rowmap, grad_loss, mean};
+                             hdr, rowmap, grad_loss, mean, p.split_dw, slice_len(n_nt * TILE, p.split_dw), partial,
+                             vc_pad * d};
   };
   // dH[row chunk] += G . W[vocab chunk]      (contraction over the vocabulary chunk)
   auto dh_args = [&](int vc, int nc, const T* Gb) {
@@ -287,10 +323,12 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     if constexpr (L::TRANSPOSING)
       return ContractArgs<T>{static_cast<const T*>(W) + (int64_t)vt0 * TILE * d, d, V - vt0 * TILE, d, Gb, vc_pad,
                              n_nt * TILE, n_vt * TILE, 0, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH), nt0 * TILE, npad,
-                             flags, hdr, rowmap, grad_loss, mean};
+                             flags, hdr, rowmap, grad_loss, mean, p.split_dh, slice_len(n_vt * TILE, p.split_dh),
+                             partial - (int64_t)nt0 * TILE * d, nc_pad * d};
     else
       return ContractArgs<T>{WT, vc_pad, 0, d, Gb, vc_pad, n_nt * TILE, n_vt * TILE, 0, n_mt, n_nt, dHacc, 0,
-                             static_cast<T*>(dH), nt0 * TILE, npad, flags, hdr, rowmap, grad_loss, mean};
+                             static_cast<T*>(dH), nt0 * TILE, npad, flags, hdr, rowmap, grad_loss, mean, p.split_dh,
+                             slice_len(n_vt * TILE, p.split_dh), partial - (int64_t)nt0 * TILE * d, nc_pad * d};
   };
 
   for (int vc = 0; vc < p.n_vch; ++vc) {
@@ -317,17 +355,19 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
         const ContractArgs<T> a = dw_args(vc, nc, G);
         ProfScope ps(FLCE_PROF_CONTRACT_DW, st);
         if constexpr (L::TRANSPOSING)
-          contract_kernel<T, L, OPS_DW_TR><<<a.n_nt * a.n_mt, L::THREADS, L::LDS, st>>>(a);
+          contract_kernel<T, L, OPS_DW_TR><<<a.n_nt * a.n_mt * a.n_split, L::THREADS, L::LDS, st>>>(a);
         else
-          contract_kernel<T, L, OPS_KC><<<a.n_nt * a.n_mt, L::THREADS, L::LDS, st>>>(a);
+          contract_kernel<T, L, OPS_KC><<<a.n_nt * a.n_mt * a.n_split, L::THREADS, L::LDS, st>>>(a);
+        if (a.n_split > 1) splitk_reduce_kernel<T><<<a.n_nt * TILE, 256, 0, st>>>(a);
       }
       {
         const ContractArgs<T> a = dh_args(vc, nc, G);
         ProfScope ps(FLCE_PROF_CONTRACT_DH, st);
         if constexpr (L::TRANSPOSING)
-          contract_kernel<T, L, OPS_DH_TR><<<a.n_nt * a.n_mt, L::THREADS, L::LDS, st>>>(a);
+          contract_kernel<T, L, OPS_DH_TR><<<a.n_nt * a.n_mt * a.n_split, L::THREADS, L::LDS, st>>>(a);
         else
-          contract_kernel<T, L, OPS_KC><<<a.n_nt * a.n_mt, L::THREADS, L::LDS, st>>>(a);
+          contract_kernel<T, L, OPS_KC><<<a.n_nt * a.n_mt * a.n_split, L::THREADS, L::LDS, st>>>(a);
+        if (a.n_split > 1) splitk_reduce_kernel<T><<<a.n_nt * TILE, 256, 0, st>>>(a);
       }
     }
   }

@@ -518,6 +518,10 @@ struct ContractArgs {
   float* accbuf; int acc_row0;
   T* out; int out_row0, out_rows, flags;
   const Header* hdr; const int* rowmap; float grad_loss; int mean;
+  // split-K (n_split > 1): the launch has n_split x tiles workgroups; slice z contracts K elements
+  // [z * k_split, (z + 1) * k_split) and stores its fp32 tile into partial + z * partial_stride (indexed like
+  // accbuf); splitk_reduce_kernel then adds the slices in slice order and does the READ/WRITE part of `flags`.
+  int n_split, k_split; float* partial; int64_t partial_stride;
 };
 
 template <typename T, typename L, int OPS>
@@ -525,30 +529,43 @@ __device__ __forceinline__ void contract_tile(const ContractArgs<T>& a, int bid,
   const T* __restrict__ A = a.A; const T* __restrict__ B = a.B;
   const int64_t lda = a.lda, ldb = a.ldb;
   const int a_krows = a.a_krows, d = a.d, b_rows = a.b_rows, k_start = a.k_start, acc_row0 = a.acc_row0;
-  const int out_row0 = a.out_row0, out_rows = a.out_rows, flags = a.flags, mean = a.mean;
+  const int out_row0 = a.out_row0, out_rows = a.out_rows, mean = a.mean;
+  int flags = a.flags;
   int k_elems = a.k_elems;
   float* __restrict__ accbuf = a.accbuf; T* __restrict__ out = a.out;
   const Header* __restrict__ hdr = a.hdr; const int* __restrict__ rowmap = a.rowmap;
   const float grad_loss = a.grad_loss;
-  const int id = xcd_contiguous_id(bid, nblocks);
+  const int tiles = a.n_nt * a.n_mt;
+  const int z = a.n_split > 1 ? bid / tiles : 0;             // K slice of this workgroup
+  const int id = xcd_contiguous_id(bid - z * tiles, tiles);
+  (void)nblocks;
   int p, q;                                    // output-row tile, hidden tile
   grouped_raster(id, a.n_nt, a.n_mt, 8, p, q);
   const int nv = (int)hdr->n_valid;
   if ((flags & ROWS_COMPACT) && out_row0 + p * TILE >= nv) return;
   if (flags & K_COMPACT) k_elems = max(0, min(k_elems, (nv - k_start + TILE - 1) / TILE * TILE));
+  int k0 = 0;
+  if (a.n_split > 1) {
+    k0 = z * a.k_split;
+    k_elems = max(0, min(a.k_split, k_elems - k0));
+    accbuf = a.partial + (int64_t)z * a.partial_stride;
+    flags = (flags & ROWS_COMPACT) | WRITE_ACC;
+  }
   f32x16 acc[L::WM][L::WN];
   if constexpr (OPS == OPS_KC) {
-    L::run(A, lda * (int64_t)sizeof(T), q * TILE, d, B, ldb * (int64_t)sizeof(T), p * TILE, b_rows,
+    L::run(A + k0, lda * (int64_t)sizeof(T), q * TILE, d, B + k0, ldb * (int64_t)sizeof(T), p * TILE, b_rows,
            k_elems * (int)sizeof(T), lds, acc);
   } else {
-    // A: K rows start at A (a_rows = b_rows_or_k valid from there), window of 256 hidden columns at q
+    // A: K rows start at A (a_krows valid from there), window of 256 hidden columns at q
     const int width = max(0, min(TILE, d - q * TILE)) * 2;
-    const fast::Operand As{reinterpret_cast<const char*>(A) + (int64_t)q * TILE * 2, lda * 2, 0, a_krows, width};
+    const fast::Operand As{reinterpret_cast<const char*>(A + (int64_t)k0 * lda) + (int64_t)q * TILE * 2, lda * 2, 0,
+                           a_krows - k0, width};
     if constexpr (OPS == OPS_DH_TR) {
-      const fast::Operand Bs{reinterpret_cast<const char*>(B), ldb * 2, p * TILE, b_rows, 0};
+      const fast::Operand Bs{reinterpret_cast<const char*>(B + k0), ldb * 2, p * TILE, b_rows, 0};
       fast::mainloop<fast::KR, fast::KC>(As, Bs, k_elems, lds, acc);
     } else {
-      const fast::Operand Bs{reinterpret_cast<const char*>(B) + (int64_t)p * TILE * 2, ldb * 2, 0, b_rows, TILE * 2};
+      const fast::Operand Bs{reinterpret_cast<const char*>(B + (int64_t)k0 * ldb) + (int64_t)p * TILE * 2, ldb * 2, 0,
+                             b_rows - k0, TILE * 2};
       fast::mainloop<fast::KR, fast::KR>(As, Bs, k_elems, lds, acc);
     }
   }
@@ -588,6 +605,36 @@ template <typename T, typename L, int OPS>
 __global__ __launch_bounds__(L::THREADS) void contract_kernel(ContractArgs<T> a) {
   extern __shared__ __align__(16) char lds[];
   contract_tile<T, L, OPS>(a, blockIdx.x, gridDim.x, lds);
+}
+
+// Second half of a split-K contraction: one block per output row of the launch; adds the K
+// slices in slice order (fixed), then the running sum / Gamma / rounding exactly as the
+// unsplit epilogue would.
+template <typename T>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(ContractArgs<T> a) {
+  const int n = a.out_row0 + blockIdx.x;
+  if (n >= a.out_rows) return;
+  const int nv = (int)a.hdr->n_valid;
+  int64_t orow = n;
+  if (a.flags & ROWS_COMPACT) {
+    if (n >= nv) return;
+    orow = a.rowmap[n];
+    if (orow < 0) return;
+  }
+  float scale = a.grad_loss;
+  if (a.mean) scale = nv > 0 ? a.grad_loss / (float)nv : 0.f;
+  const int d = a.d;
+  for (int m = threadIdx.x * 4; m < d; m += 256 * 4) {
+    const int64_t off = (int64_t)(n - a.acc_row0) * d + m;
+    f32x4 v = *reinterpret_cast<const f32x4*>(a.partial + off);
+    for (int z = 1; z < a.n_split; ++z) v += *reinterpret_cast<const f32x4*>(a.partial + z * a.partial_stride + off);
+    float* ap = a.accbuf + off;
+    if (a.flags & READ_ACC) v += *reinterpret_cast<const f32x4*>(ap);
+    if (a.flags & WRITE_ACC) *reinterpret_cast<f32x4*>(ap) = v;
+    if (a.flags & WRITE_OUT)
+      Pack4<T>::store(a.out + orow * d + m, v[0] * scale + 0.f, v[1] * scale + 0.f, v[2] * scale + 0.f,
+                      v[3] * scale + 0.f);
+  }
 }
 
 }  // namespace flce

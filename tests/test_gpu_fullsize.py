@@ -29,7 +29,7 @@ from paper_2511_17599_amd.runner import session_for, to_host_f64   # noqa: E402
 def _need_gpu(monkeypatch):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    for k in ("FLCE_WINDOWS", "FLCE_VC_TILES", "FLCE_NC_TILES", "FLCE_GENERIC"):
+    for k in ("FLCE_WINDOWS", "FLCE_VC_TILES", "FLCE_NC_TILES", "FLCE_GENERIC", "FLCE_SPLITK_DH", "FLCE_SPLITK_DW"):
         monkeypatch.delenv(k, raising=False)
     yield
 

@@ -26,7 +26,7 @@ TOL = {"f32": dict(loss=1e-5, grad=1e-4, lse=2e-6), "bf16": dict(loss=2e-3, grad
 def _need_gpu_and_clean_env(monkeypatch):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    for k in ("FLCE_WINDOWS", "FLCE_VC_TILES", "FLCE_NC_TILES", "FLCE_GENERIC"):
+    for k in ("FLCE_WINDOWS", "FLCE_VC_TILES", "FLCE_NC_TILES", "FLCE_GENERIC", "FLCE_SPLITK_DH", "FLCE_SPLITK_DW"):
         monkeypatch.delenv(k, raising=False)
     yield
 
@@ -99,6 +99,20 @@ def test_chunk_and_window_splits(monkeypatch, dtype, generic, windows, vc, nc):
     monkeypatch.setenv("FLCE_NC_TILES", str(nc))
     monkeypatch.setenv("FLCE_GENERIC", str(generic))
     wl = custom(f"split_{dtype}_{generic}_{windows}_{vc}_{nc}", 700, 160, 1500, dtype, 21, ignore_frac=0.05)
+    check_against_oracle(wl, I.make_inputs(wl))
+
+
+@pytest.mark.parametrize("dtype,generic", [("bf16", 0), ("bf16", 1), ("f32", 0)])
+@pytest.mark.parametrize("sdh,sdw,vc,nc", [(3, 2, 128, 32), (2, 3, 4, 2), (5, 1, 2, 1)])
+def test_split_k_contractions(monkeypatch, dtype, generic, sdh, sdw, vc, nc):
+    """K of the dH / dW contractions cut into slices whose fp32 tiles are summed in slice order, with and
+    without chunk accumulation on top."""
+    monkeypatch.setenv("FLCE_SPLITK_DH", str(sdh))
+    monkeypatch.setenv("FLCE_SPLITK_DW", str(sdw))
+    monkeypatch.setenv("FLCE_VC_TILES", str(vc))
+    monkeypatch.setenv("FLCE_NC_TILES", str(nc))
+    monkeypatch.setenv("FLCE_GENERIC", str(generic))
+    wl = custom(f"splitk_{dtype}_{generic}_{sdh}_{sdw}_{vc}_{nc}", 1100, 288, 1800, dtype, 22, ignore_frac=0.08)
     check_against_oracle(wl, I.make_inputs(wl))
 
 
