@@ -255,8 +255,8 @@ struct Pipe {
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int s = 0; s < 16; ++s) {
-        acc[s >> 2][s & 3] =
-            __builtin_amdgcn_mfma_f32_32x32x16_bf16(FM.a[s >> 2], FM.b[s & 3], acc[s >> 2][s & 3], 0, 0, 0);
+        const int mi = s >> 2, mj = s & 3;
+        acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FM.a[mi], FM.b[mj], acc[mi][mj], 0, 0, 0);
         // reads t with t * 16 / RT == s: spread evenly over the 16 slots
 #pragma unroll
         for (int t = 0; t < RT; ++t)
