@@ -7,12 +7,15 @@
 //             Section 3.2.1, lse = m + ln a, per-row loss, fixed-order sums)
 //   backward: compact_targets_kernel + gather_rows_kernel (n_valid, range flag, and the
 //             rows that count packed together: ignored rows have a zero row of G)
-//             transpose_pad_kernel (K-contiguous copies of H and W for the two
-//             gradient contractions)
-//             recompute_kernel (Alg. 2: z recomputed, g = p - onehot, written once to
-//             a fixed-size staging tile in both orientations)
+//             transpose_pad_kernel (the transposed copy of H that the tuned main loop
+//             reads across memory rows; with the generic loop also the K-contiguous
+//             copies of W and H that the two gradient contractions need)
+//             recompute_kernel (Alg. 2: z recomputed, g = p - onehot, staged once in a
+//             fixed-size buffer; the generic loop also stages the transpose)
 //             contract_kernel (Eq. 4 and Eq. 5 as output-stationary MFMA
 //             contractions with a fixed chunk order; Gamma applied at the flush)
+//             splitk_reduce_kernel (fixed-order sum of K slices when a contraction
+//             launch would otherwise leave most CUs idle)
 #pragma once
 #include <type_traits>
 
