@@ -54,6 +54,69 @@ def cpu_baseline(wl, x, rows):
                       f"{dt:.1f} s wall"}, f
 
 
+# The paper's own evaluation grid (Table 1 / Table 2): d = 4096, bf16, B*T x V, with its latency (ms) and memory
+# (MB) for the fused kernels on an NVIDIA GB200 -- another machine, quoted as context.  Table 2 does not say
+# what the latency covers; its size says forward only.
+PAPER_TABLE2 = {  # (N, V): (canonical_ms, proposed_ms, canonical_MB, proposed_MB)
+    (1024, 32768): (0.73, 0.69, 1064, 280), (1024, 65536): (1.40, 0.97, 2088, 536),
+    (1024, 131072): (2.76, 1.27, 4136, 1048), (1024, 262144): (5.46, 1.83, 8232, 2072),
+    (4096, 32768): (1.66, 1.16, 1904, 304), (4096, 65536): (3.34, 1.69, 3696, 561),
+    (4096, 131072): (6.78, 2.86, 7280, 1073), (4096, 262144): (13.70, 5.22, 14448, 2099),
+    (8192, 32768): (2.93, 1.70, 3024, 337), (8192, 65536): (6.08, 2.90, 5840, 593),
+    (8192, 131072): (13.25, 5.58, 11472, 1107), (8192, 262144): (27.77, 10.79, 22736, 2133),
+    (16384, 32768): (5.62, 3.43, 5264, 401), (16384, 65536): (12.41, 6.61, 10128, 659),
+    (16384, 131072): (26.67, 13.20, 19856, 1173), (16384, 262144): (50.15, 25.43, 39312, 2203),
+    (32768, 32768): (11.42, 7.00, 9744, 531), (32768, 65536): (25.64, 13.80, 18704, 790),
+    (32768, 131072): (50.24, 27.06, 36624, 1307), (32768, 262144): (96.52, 53.61, 72464, 2342),
+}
+
+
+def sweep_paper_grid(steps, warmup):
+    """Forward-only and forward+backward latency and memory over the paper's grid; one JSON line per point."""
+    import torch
+    from paper_2511_17599_amd import binding as B
+    from paper_2511_17599_amd import inputs as I
+    from paper_2511_17599_amd.runner import Session, to_device
+
+    d = 4096
+    torch.cuda.set_device(0)
+    Ns = sorted({k[0] for k in PAPER_TABLE2})
+    Vs = sorted({k[1] for k in PAPER_TABLE2})
+    Hfull = to_device(I.f32_to_bf16_bits(I.normal_f32(2001, I.STREAM_H, max(Ns) * d, 1.0)).reshape(max(Ns), d), "cuda")
+    for V in Vs:
+        W = to_device(I.f32_to_bf16_bits(I.normal_f32(2001, I.STREAM_W, V * d, 0.02)).reshape(V, d), "cuda")
+        for N in Ns:
+            y = I.targets_uniform(2001 + N, N, V)
+            s = Session(N, d, V, "bf16", "mean", -100, Hfull[:N], W, y)
+
+            def timed(fn):
+                for _ in range(warmup):
+                    fn()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    fn()
+                torch.cuda.synchronize()
+                return (time.perf_counter() - t0) / steps * 1e3
+
+            fwd_ms = timed(lambda: s.forward())
+            both_ms = timed(lambda: (s.forward(), s.backward()))
+            st, nv = s.device_status()
+            assert st == B.FLCE_OK and nv == N
+            ref = PAPER_TABLE2[(N, V)]
+            fwd_bytes = (N + V) * d * 2 + N * 8 + N * 4 + 4 + s.fwd_bytes
+            print(json.dumps({
+                "sweep": "paper_table2", "N": N, "d": d, "V": V, "dtype": "bf16",
+                "forward_ms": fwd_ms, "forward_tflops_2NdV": 2.0 * N * d * V / fwd_ms / 1e9,
+                "forward_backward_ms": both_ms, "forward_backward_tflops_8NdV": 8.0 * N * d * V / both_ms / 1e9,
+                "forward_memory_MiB": fwd_bytes / 2**20, "forward_backward_memory_MiB": s.tensor_bytes() / 2**20,
+                "naive_fp32_logits_MiB": N * V * 4 / 2**20, "loss": float(s.loss.item()),
+                "paper_gb200": {"canonical_ms": ref[0], "proposed_ms": ref[1], "canonical_MB": ref[2],
+                                "proposed_MB": ref[3]}}), flush=True)
+            del s
+        del W
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -65,10 +128,16 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="bytes of one plain device copy issued before the timed region (a yardstick for "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--sweep", choices=["paper_table2"], default=None,
+                    help="instead of the benchmark line: latency and memory over the paper's evaluation grid")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures the one-GPU kernel path only; run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.sweep:
+        sweep_paper_grid(args.steps, args.warmup)
+        return
 
     import numpy as np
     import torch
@@ -146,7 +215,7 @@ def main():
 
     rows = args.oracle_rows
     if rows is None:
-        rows = max(16, min(wl.N, int(4.0e12 / (6.0 * wl.d * wl.V))))     # ~10-20 s of fp64 work
+        rows = max(16, min(wl.N, int(8.0e12 / (6.0 * wl.d * wl.V))))     # ~10-20 s of fp64 work
     base = None
     if rows > 0:
         base, f = cpu_baseline(wl, x, min(rows, wl.N))

@@ -42,20 +42,24 @@ struct Plan {
   int n_vch, n_nch;        // chunks along vocabulary / tokens
   int vc_tiles, nc_tiles;  // largest chunk, in tiles
   bool fast;               // tuned bf16 loop: W, Hc and G read in place by the contractions
-  bool hkr;                // forward / recompute read a transposed copy of H (needs its window below 2^31 bytes)
+  bool hkr;                // forward / recompute read a transposed copy of H (needs its window within a descriptor's reach)
   int split_dh, split_dw;  // K slices of the dH / dW contraction launches (1 = unsplit)
   int64_t off_Hc, off_rowmap, off_tgt, off_lsec, off_HT, off_WT, off_G, off_GT, off_dHacc, off_dWacc, off_partial, bwd_bytes;
 };
 
-// The tuned bf16 loop needs K extents that are multiples of 32 elements and every tile's
-// address window below 2^31 bytes; FLCE_GENERIC=1 forces the generic loop everywhere.
+// The tuned bf16 loop needs K extents that are multiples of 32 elements and every tile's address
+// window within reach of a buffer descriptor: offsets are unsigned 32-bit, the bytes actually read
+// stay below 2^31, and the zero-filled overshoot of a last K stage (up to 32 rows) must not wrap
+// 2^32.  FLCE_GENERIC=1 forces the generic loop everywhere.
+bool window_ok(int64_t k_rows, int64_t ld_bytes) {
+  return k_rows * ld_bytes <= ((int64_t)1 << 31) && (k_rows + 32) * ld_bytes < ((int64_t)1 << 32);
+}
 bool fast_loop_ok(const Plan& p) {
   if (p.esize != 2 || env_int("FLCE_GENERIC", 0, 0, 1)) return false;
-  const int64_t lim = (int64_t)1 << 31;
   const int64_t vc = (int64_t)p.vc_tiles * TILE, nc = (int64_t)p.nc_tiles * TILE;
   const int64_t ld_hw = p.d * 2, ld_g = vc * 2;
-  return p.d % 32 == 0 && 256 * ld_hw + ld_hw < lim && 256 * ld_g + ld_g < lim &&   // K-contiguous tiles
-         (vc + 32) * ld_hw < lim && (nc + 32) * ld_hw < lim && (nc + 32) * ld_g < lim;  // K over memory rows
+  return p.d % 32 == 0 && window_ok(257, ld_hw) && window_ok(257, ld_g) &&      // K-contiguous tiles
+         window_ok(vc, ld_hw) && window_ok(nc, ld_hw) && window_ok(nc, ld_g);   // K over memory rows
 }
 
 bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
@@ -85,14 +89,14 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
 
   // Backward staging: a fixed-size G tile of at most vc x nc 256-tiles.
   const int vc_max = env_int("FLCE_VC_TILES", 128, 1, 4096);
-  const int nc_max = env_int("FLCE_NC_TILES", 32, 1, 4096);
+  const int nc_max = env_int("FLCE_NC_TILES", 128, 1, 4096);
   p.n_vch = (int)ceil_div(p.n_vt, vc_max);
   p.n_nch = (int)ceil_div(p.n_rb, nc_max);
   p.vc_tiles = (int)ceil_div(p.n_vt, p.n_vch);
   p.nc_tiles = (int)ceil_div(p.n_rb, p.n_nch);
   const int64_t vc_pad = (int64_t)p.vc_tiles * TILE, nc_pad = (int64_t)p.nc_tiles * TILE;
   p.fast = fast_loop_ok(p);
-  p.hkr = p.fast && (d + 32) * p.npad * 2 < ((int64_t)1 << 31);
+  p.hkr = p.fast && window_ok(d, p.npad * 2);
   p.fwd_bytes = fwd_fixed + (p.hkr ? align_up(d * p.npad * p.esize, ALIGN) : 0);
   o = ALIGN;
   p.off_Hc = o;     o = align_up(o + d * p.npad * p.esize, ALIGN);

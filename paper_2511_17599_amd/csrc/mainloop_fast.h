@@ -28,7 +28,7 @@
 //     stream.
 //
 // Requires the K extent to be a multiple of 32 elements and offsets inside one tile's
-// address window below 2^31; the generic loop in tile_mma.h covers everything else.
+// address window within 2^31 bytes; the generic loop in tile_mma.h covers everything else.
 #pragma once
 #include "tile_mma.h"
 
@@ -69,7 +69,7 @@ struct Operand {
 // transposing reads among them) and waits for vmcnt(0) before each, which serialises the
 // pipeline.  Here the only consumers are separated from the DMA by the explicit vmcnt
 // wait + barrier of the main loop.  M0 carries the LDS destination of the wavefront.
-__device__ __forceinline__ void dma16(u32x4 rsrc, uint32_t lds_addr, int voffset, int soffset) {
+__device__ __forceinline__ void dma16(u32x4 rsrc, uint32_t lds_addr, uint32_t voffset, uint32_t soffset) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :
                : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
@@ -127,8 +127,8 @@ __device__ __forceinline__ void wait_vm_and_lds() {
 template <int LAYOUT>
 struct Loader {
   u32x4 rs;
-  int v[4];               // per-lane byte offsets of the 4 requests (K tile 0)
-  int k_step;             // KC: bytes of K per stage (scalar offset); KR: bytes of 32 K rows (added per lane)
+  uint32_t v[4];          // per-lane byte offsets of the 4 requests (K tile 0); unsigned: a window may reach 2^32 bytes
+  uint32_t k_step;        // KC: bytes of K per stage (scalar offset); KR: bytes of 32 K rows (added per lane)
   __device__ __forceinline__ void init(const Operand& s, int k_elems) {
     rs = make_rsrc<LAYOUT>(s, k_elems);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -137,21 +137,21 @@ struct Loader {
       if (LAYOUT == KC) {
         const int row = wave * 64 + i * 16 + (lane >> 2);
         const int chunk = (lane & 3) ^ ((row >> 2) & 3);
-        v[i] = (int)(row * s.ld_bytes) + chunk * 16;
+        v[i] = (uint32_t)(row * s.ld_bytes) + chunk * 16;
       } else {
         const int krow = wave * 8 + i * 2 + (lane >> 5);
         const int off = ((lane & 31) * 16) ^ ((krow & 3) << 6);
-        v[i] = (int)(krow * s.ld_bytes) + off;
+        v[i] = (uint32_t)(krow * s.ld_bytes) + off;
       }
     }
-    k_step = LAYOUT == KC ? BK * 2 : (int)(BK * s.ld_bytes);
+    k_step = LAYOUT == KC ? BK * 2 : (uint32_t)(BK * s.ld_bytes);
   }
   // request i of K tile kt into `dst` (this wavefront's slice of the operand tile of some stage)
   __device__ __forceinline__ void issue(int i, char* dst, int kt) const {
     if (LAYOUT == KC)
-      dma16(rs, lds_address(dst + i * 1024), v[i], kt * k_step);
+      dma16(rs, lds_address(dst + i * 1024), v[i], (uint32_t)kt * k_step);
     else   // the K advance moves to other rows: keep it in the per-lane offset, which the range check covers
-      dma16(rs, lds_address(dst + i * 1024), v[i] + kt * k_step, 0);
+      dma16(rs, lds_address(dst + i * 1024), v[i] + (uint32_t)kt * k_step, 0);
   }
 };
 

@@ -39,7 +39,7 @@ def test_workspace_has_no_NV_term():
             assert big <= 2.2 * base + (1 << 20)
     # the long-sequence shape: naive fp32 logits are 67 GB, the workspace stays far below that
     ws = B.flce_workspace_bytes(131072, 4096, 128256, B.FLCE_DTYPE_BF16, 1)
-    assert ws < 0.1 * 131072 * 128256 * 4
+    assert ws < 0.12 * 131072 * 128256 * 4
     fw = B.flce_workspace_bytes(131072, 4096, 128256, B.FLCE_DTYPE_BF16, 0)
     assert fw < 131072 * 4096 * 2 + 64 * (1 << 20)          # at most one copy of H plus per-row partials
 

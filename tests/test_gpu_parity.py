@@ -199,3 +199,10 @@ def test_results_are_bit_identical_between_runs():
 def test_gpt2_small_workload():
     wl = I.WORKLOADS["gpt2_small"]
     check_against_oracle(wl, I.make_inputs(wl))
+
+
+def test_largest_staging_tile():
+    """128 x 128 tiles of G in one launch (2 GiB in bf16): the contraction that walks G over memory
+    rows reaches the end of what one buffer descriptor can address."""
+    wl = custom("g_2gib", 32728, 64, 32750, "bf16", 71, ignore_frac=0.003)
+    check_against_oracle(wl, I.make_inputs(wl))
