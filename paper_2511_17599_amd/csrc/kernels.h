@@ -448,11 +448,17 @@ __device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bi
   const int* __restrict__ tgt_c = a.tgt_c; const float* __restrict__ lse_c = a.lse_c;
   const int npad = a.npad, d = a.d, V = a.V;
   T* __restrict__ G = a.G; T* __restrict__ GT = a.GT; const int64_t ldG = a.ldG, ldGT = a.ldGT;
-  const int id = xcd_contiguous_id(bid, nblocks);
+  // Only the row tiles that hold counted rows are rastered (their number is known on the device
+  // alone), so the XCDs share the work evenly however many rows are ignored; the surplus
+  // workgroups of the launch, sized for N rows, leave at once.
+  (void)nblocks;
+  const int n_nt = max(0, min(a.n_nt, ((int)a.hdr->n_valid - a.nt0 * TILE + TILE - 1) / TILE));
+  const int useful = n_nt * a.n_vt;
+  if (bid >= useful) return;
+  const int id = xcd_contiguous_id(bid, useful);
   int p, q;                                    // row tile, vocabulary tile inside the chunk
-  grouped_raster(id, a.n_nt, a.n_vt, 8, p, q);
+  grouped_raster(id, n_nt, a.n_vt, 8, p, q);
   const int n0 = (a.nt0 + p) * TILE, v0 = (a.vt0 + q) * TILE;
-  if (n0 >= (int)a.hdr->n_valid) return;
   const int64_t ld_bytes = (int64_t)d * sizeof(T);
   f32x16 acc[L::WM][L::WN];
   if constexpr (HKR) L::run_bt(W, ld_bytes, v0, V, HcT, (int64_t)npad * sizeof(T), n0, d, lds, acc);
@@ -538,14 +544,19 @@ __device__ __forceinline__ void contract_tile(const ContractArgs<T>& a, int bid,
   float* __restrict__ accbuf = a.accbuf; T* __restrict__ out = a.out;
   const Header* __restrict__ hdr = a.hdr; const int* __restrict__ rowmap = a.rowmap;
   const float grad_loss = a.grad_loss;
-  const int tiles = a.n_nt * a.n_mt;
-  const int z = a.n_split > 1 ? bid / tiles : 0;             // K slice of this workgroup
-  const int id = xcd_contiguous_id(bid - z * tiles, tiles);
   (void)nblocks;
-  int p, q;                                    // output-row tile, hidden tile
-  grouped_raster(id, a.n_nt, a.n_mt, 8, p, q);
   const int nv = (int)hdr->n_valid;
-  if ((flags & ROWS_COMPACT) && out_row0 + p * TILE >= nv) return;
+  // With compacted output rows only the row tiles that hold counted rows are rastered, so the
+  // XCDs share the work evenly; surplus workgroups of the launch leave at once.
+  int n_nt = a.n_nt;
+  if (flags & ROWS_COMPACT) n_nt = max(0, min(n_nt, (nv - out_row0 + TILE - 1) / TILE));
+  const int tiles = n_nt * a.n_mt;
+  if (tiles == 0) return;
+  const int z = bid / tiles;                                 // K slice of this workgroup
+  if (z >= max(1, a.n_split)) return;
+  const int id = xcd_contiguous_id(bid - z * tiles, tiles);
+  int p, q;                                    // output-row tile, hidden tile
+  grouped_raster(id, n_nt, a.n_mt, 8, p, q);
   if (flags & K_COMPACT) k_elems = max(0, min(k_elems, (nv - k_start + TILE - 1) / TILE * TILE));
   int k0 = 0;
   if (a.n_split > 1) {
