@@ -128,6 +128,9 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="bytes of one plain device copy issued before the timed region (a yardstick for "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--path", choices=["recompute", "partial_grads"], default="recompute",
+                    help="recompute: forward (Alg. 1) + backward (Alg. 2), the benchmarked path; partial_grads: "
+                         "forward with partial gradients (Alg. 3) + scaling (Alg. 4)")
     ap.add_argument("--sweep", choices=["paper_table2"], default=None,
                     help="instead of the benchmark line: latency and memory over the paper's evaluation grid")
     args = ap.parse_args()
@@ -152,9 +155,14 @@ def main():
     s = session_for(wl, x)
 
     def step():
-        st = s.forward()
-        assert st == B.FLCE_OK, B.flce_status_string(st)
-        st = s.backward()
+        if args.path == "partial_grads":
+            st = s.forward_with_grads()
+            assert st == B.FLCE_OK, B.flce_status_string(st)
+            st = s.scale()
+        else:
+            st = s.forward()
+            assert st == B.FLCE_OK, B.flce_status_string(st)
+            st = s.backward()
         assert st == B.FLCE_OK, B.flce_status_string(st)
 
     if args.copy_calibration:
@@ -199,7 +207,7 @@ def main():
             ms_step = prof_ms[k] / args.steps
             kernels[k] = {"ms_per_step": ms_step, "launches_per_step": prof_n[k] / args.steps,
                           "tflops": c * wl.N * wl.d * wl.V / (ms_step * 1e-3) / 1e12}
-    for k in ("fwd_epilogue", "bwd_prep"):
+    for k in ("fwd_epilogue", "bwd_prep", "scale"):
         if prof_n.get(k):
             kernels[k] = {"ms_per_step": prof_ms[k] / args.steps, "launches_per_step": prof_n[k] / args.steps}
     roofline = None
@@ -228,7 +236,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "d": wl.d, "V": wl.V, "reduction": wl.reduction,
-                   "targets": wl.targets, "ignore_frac": wl.ignore_frac, "seed": wl.seed},
+                   "targets": wl.targets, "ignore_frac": wl.ignore_frac, "seed": wl.seed, "path": args.path},
         "tflops_8NdV": tflops, "frac_of_mfma_peak": tflops / peak,
         "tflops_executed": flops_executed / (ms_per_step * 1e-3) / 1e12,
         "flops_note": "8NdV counts the ignored rows too; the backward skips them (their rows of G are zero), "

@@ -109,6 +109,40 @@ flce_status flce_backward(const void* H, const void* W, const int64_t* targets, 
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Forward with partial gradient accumulation (Alg. 3): the loss and lse of flce_forward
+ * plus the gradients not yet scaled by the upstream gradient,
+ *   dH_partial[i] = sum_v (P_iv - 1[v = y_i]) W_v,   dW_partial[v] = sum_i (P_iv - 1[v = y_i]) H_i,
+ * over the counted rows (rows that do not count get a zero row of dH_partial and add nothing
+ * to dW_partial).  Only meaningful when the upstream gradient is a scalar, i.e. for the mean
+ * and sum reductions this library has (Section "Backward", remark before Alg. 3).
+ *   dH_partial : device, N*d elements of type dt.   dW_partial : device, V*d elements of type dt.
+ *   workspace  : device, at least max(flce_workspace_bytes(.., 0), flce_workspace_bytes(.., 1))
+ *                bytes; its header afterwards holds n_valid for flce_scale.
+ * The partial sums are rounded once to `dt` here and once more by flce_scale; flce_forward +
+ * flce_backward round once (Gamma is applied to the fp32 sums) and are the cheaper pair on
+ * this implementation: the second sweep of Alg. 3 recomputes the logits either way.
+ */
+flce_status flce_forward_with_grads(const void* H, const void* W, const int64_t* targets,
+                                    int64_t N, int64_t d, int64_t V, int64_t ignore_index,
+                                    flce_reduction reduction, flce_dtype dt,
+                                    float* loss_out, float* lse_out,
+                                    void* dH_partial, void* dW_partial,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward scaling (Alg. 4, scalar branch): dH_out = Gamma * dH_partial, dW_out = Gamma * dW_partial
+ * with Gamma = grad_loss / n_valid (mean; 0 when no row counts) or grad_loss (sum), n_valid read
+ * on the device from the header of the workspace flce_forward_with_grads used.
+ *   grad_loss : upstream gradient of the scalar loss (host value).
+ *   dH_out, dW_out : device; may be the partial buffers themselves (in place).
+ * Elementwise: reads and writes each element once.
+ */
+flce_status flce_scale(const void* dH_partial, const void* dW_partial,
+                       int64_t N, int64_t d, int64_t V,
+                       flce_reduction reduction, flce_dtype dt, float grad_loss,
+                       const void* workspace, void* dH_out, void* dW_out, void* hip_stream);
+
+/*
  * Synchronises `hip_stream`, then reports what the last flce_forward or
  * flce_backward that used `workspace` latched on the device: FLCE_OK or
  * FLCE_ERR_TARGET_RANGE (FLCE_ERR_HIP if the synchronisation or copy fails).
@@ -135,7 +169,8 @@ enum {
   FLCE_PROF_RECOMPUTE = 3,   /* backward logit recompute + G */
   FLCE_PROF_CONTRACT_DW = 4, /* dW = G^T.H */
   FLCE_PROF_CONTRACT_DH = 5, /* dH = G.W */
-  FLCE_PROF_CLASSES = 6
+  FLCE_PROF_SCALE = 6,       /* Alg. 4 scaling pass */
+  FLCE_PROF_CLASSES = 7
 };
 flce_status flce_profile_enable(int on);
 flce_status flce_profile_collect(double* ms_by_class, int64_t* launches_by_class);

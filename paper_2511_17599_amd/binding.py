@@ -19,8 +19,9 @@ FLCE_DTYPE_BF16, FLCE_DTYPE_F32 = 0, 1
 FLCE_REDUCE_MEAN, FLCE_REDUCE_SUM = 0, 1
 
 EXPORTS = ("flce_version", "flce_status_string", "flce_workspace_bytes", "flce_forward", "flce_backward",
-           "flce_last_device_status", "flce_profile_enable", "flce_profile_collect")
-PROF_CLASSES = ("fwd_tiles", "fwd_epilogue", "bwd_prep", "recompute", "contract_dW", "contract_dH")
+           "flce_forward_with_grads", "flce_scale", "flce_last_device_status", "flce_profile_enable",
+           "flce_profile_collect")
+PROF_CLASSES = ("fwd_tiles", "fwd_epilogue", "bwd_prep", "recompute", "contract_dW", "contract_dH", "scale")
 
 _lib = None
 
@@ -46,6 +47,13 @@ def lib():
         L.flce_backward.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
                                     c.c_int64, c.c_int, c.c_int, c.c_float, c.c_void_p, c.c_void_p, c.c_void_p,
                                     c.c_size_t, c.c_void_p]
+        L.flce_forward_with_grads.restype = c.c_int
+        L.flce_forward_with_grads.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
+                                              c.c_int64, c.c_int, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p,
+                                              c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+        L.flce_scale.restype = c.c_int
+        L.flce_scale.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_int,
+                                 c.c_float, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
         L.flce_last_device_status.restype = c.c_int
         L.flce_last_device_status.argtypes = [c.c_void_p, c.c_void_p, c.POINTER(c.c_int64)]
         L.flce_profile_enable.restype = c.c_int
@@ -95,6 +103,18 @@ def flce_backward(H, W, targets, lse, N, d, V, ignore_index, reduction, dt, grad
     return lib().flce_backward(_ptr(H), _ptr(W), _ptr(targets), _ptr(lse), N, d, V, ignore_index, reduction, dt,
                                float(grad_loss), _ptr(dH_out), _ptr(dW_out), _ptr(workspace), workspace_bytes,
                                _stream(hip_stream))
+
+
+def flce_forward_with_grads(H, W, targets, N, d, V, ignore_index, reduction, dt, loss_out, lse_out, dH_partial,
+                            dW_partial, workspace, workspace_bytes, hip_stream=None):
+    return lib().flce_forward_with_grads(_ptr(H), _ptr(W), _ptr(targets), N, d, V, ignore_index, reduction, dt,
+                                         _ptr(loss_out), _ptr(lse_out), _ptr(dH_partial), _ptr(dW_partial),
+                                         _ptr(workspace), workspace_bytes, _stream(hip_stream))
+
+
+def flce_scale(dH_partial, dW_partial, N, d, V, reduction, dt, grad_loss, workspace, dH_out, dW_out, hip_stream=None):
+    return lib().flce_scale(_ptr(dH_partial), _ptr(dW_partial), N, d, V, reduction, dt, float(grad_loss),
+                            _ptr(workspace), _ptr(dH_out), _ptr(dW_out), _stream(hip_stream))
 
 
 def flce_last_device_status(workspace, hip_stream=None):

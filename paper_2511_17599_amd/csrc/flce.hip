@@ -458,6 +458,52 @@ flce_status flce_backward(const void* H, const void* W, const int64_t* targets, 
                                                                      grad_loss, dH_out, dW_out, ws, st);
 }
 
+flce_status flce_forward_with_grads(const void* H, const void* W, const int64_t* targets, int64_t N, int64_t d,
+                                    int64_t V, int64_t ignore_index, flce_reduction reduction, flce_dtype dt,
+                                    float* loss_out, float* lse_out, void* dH_partial, void* dW_partial,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  // Alg. 3 = Alg. 1 followed by the gradient sweep with the upstream gradient left out: the forward,
+  // then the backward with Gamma = 1 (sum semantics, grad_loss 1), on the same stream and workspace.
+  flce::Plan p;
+  if (!flce::make_plan(N, d, V, dt, p)) return FLCE_ERR_BAD_SHAPE;
+  if (workspace_bytes < (size_t)std::max(p.fwd_bytes, p.bwd_bytes)) return FLCE_ERR_WORKSPACE;
+  if (!dH_partial || !dW_partial) return FLCE_ERR_BAD_ARG;
+  const flce_status st = flce_forward(H, W, targets, N, d, V, ignore_index, reduction, dt, loss_out, lse_out,
+                                      workspace, workspace_bytes, hip_stream);
+  if (st != FLCE_OK) return st;
+  return flce_backward(H, W, targets, lse_out, N, d, V, ignore_index, FLCE_REDUCE_SUM, dt, 1.0f, dH_partial,
+                       dW_partial, workspace, workspace_bytes, hip_stream);
+}
+
+flce_status flce_scale(const void* dH_partial, const void* dW_partial, int64_t N, int64_t d, int64_t V,
+                       flce_reduction reduction, flce_dtype dt, float grad_loss, const void* workspace,
+                       void* dH_out, void* dW_out, void* hip_stream) {
+  if (!dH_partial || !dW_partial || !dH_out || !dW_out || !workspace) return FLCE_ERR_BAD_ARG;
+  if (reduction != FLCE_REDUCE_MEAN && reduction != FLCE_REDUCE_SUM) return FLCE_ERR_BAD_ARG;
+  flce::Plan p;
+  if (!flce::make_plan(N, d, V, dt, p)) return FLCE_ERR_BAD_SHAPE;
+  if (!flce::aligned16(dH_partial) || !flce::aligned16(dW_partial) || !flce::aligned16(dH_out) ||
+      !flce::aligned16(dW_out))
+    return FLCE_ERR_BAD_ARG;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const flce::Header* hdr = static_cast<const flce::Header*>(workspace);
+  const int mean = reduction == FLCE_REDUCE_MEAN;
+  auto run = [&](auto tag) {
+    using T = decltype(tag);
+    flce::ProfScope ps(FLCE_PROF_SCALE, st);
+    const int64_t nh = N * d / 4, nw = V * d / 4;
+    const unsigned gh = (unsigned)std::min<int64_t>(flce::ceil_div(nh, 256), 16384);
+    const unsigned gw = (unsigned)std::min<int64_t>(flce::ceil_div(nw, 256), 16384);
+    flce::scale_kernel<T><<<gh, 256, 0, st>>>(static_cast<const T*>(dH_partial), static_cast<T*>(dH_out), nh, hdr,
+                                              grad_loss, mean);
+    flce::scale_kernel<T><<<gw, 256, 0, st>>>(static_cast<const T*>(dW_partial), static_cast<T*>(dW_out), nw, hdr,
+                                              grad_loss, mean);
+  };
+  if (dt == FLCE_DTYPE_BF16) run(flce::bf16_t{});
+  else run(float{});
+  return hipGetLastError() == hipSuccess ? FLCE_OK : FLCE_ERR_HIP;
+}
+
 flce_status flce_last_device_status(const void* workspace, void* hip_stream, int64_t* n_valid_out) {
   if (!workspace) return FLCE_ERR_BAD_ARG;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);

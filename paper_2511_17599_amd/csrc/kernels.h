@@ -16,6 +16,7 @@
 //             contractions with a fixed chunk order; Gamma applied at the flush)
 //             splitk_reduce_kernel (fixed-order sum of K slices when a contraction
 //             launch would otherwise leave most CUs idle)
+//   Alg. 3/4: the forward and the backward above with Gamma = 1, then scale_kernel
 #pragma once
 #include <type_traits>
 
@@ -410,6 +411,10 @@ template <> struct Pack4<float> {
   static __device__ __forceinline__ void store(float* p, float a, float b, float c, float d) {
     *reinterpret_cast<f32x4*>(p) = f32x4{a, b, c, d};
   }
+  static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
+    const f32x4 x = *reinterpret_cast<const f32x4*>(p);
+    v[0] = x[0]; v[1] = x[1]; v[2] = x[2]; v[3] = x[3];
+  }
   static __device__ __forceinline__ float one(float v) { return v; }
 };
 template <> struct Pack4<bf16_t> {
@@ -418,6 +423,11 @@ template <> struct Pack4<bf16_t> {
     v.x = (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
     v.y = (uint32_t)f32_to_bf16_bits(c) | ((uint32_t)f32_to_bf16_bits(d) << 16);
     *reinterpret_cast<uint2*>(p) = v;
+  }
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[4]) {
+    const uint2 x = *reinterpret_cast<const uint2*>(p);
+    v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xFFFF0000u);
+    v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xFFFF0000u);
   }
   static __device__ __forceinline__ bf16_t one(float v) { return bf16_t{f32_to_bf16_bits(v)}; }
 };
@@ -441,7 +451,7 @@ struct RecomputeArgs {
   T* G; int64_t ldG; T* GT; int64_t ldGT;
 };
 
-// One tile of the recompute step; `bid` of `nblocks` tiles of this launch (or of this part of a fused launch).
+// One tile of the recompute step; `bid` of `nblocks` tiles of this launch.
 template <typename T, typename L, bool HKR>
 __device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bid, int nblocks, char* lds) {
   const T* __restrict__ Hc = a.Hc; const T* __restrict__ HcT = a.HcT; const T* __restrict__ W = a.W;
@@ -648,6 +658,20 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(ContractArgs<T> a) {
     if (a.flags & WRITE_OUT)
       Pack4<T>::store(a.out + orow * d + m, v[0] * scale + 0.f, v[1] * scale + 0.f, v[2] * scale + 0.f,
                       v[3] * scale + 0.f);
+  }
+}
+
+// Alg. 4, scalar branch: out = Gamma * in, elementwise, Gamma from the header's n_valid.
+template <typename T>
+__global__ __launch_bounds__(256) void scale_kernel(const T* __restrict__ in, T* __restrict__ out, int64_t n4,
+                                                    const Header* __restrict__ hdr, float grad_loss, int mean) {
+  const int nv = (int)hdr->n_valid;
+  float scale = grad_loss;
+  if (mean) scale = nv > 0 ? grad_loss / (float)nv : 0.f;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+    float v[4];
+    Pack4<T>::load(in + i * 4, v);
+    Pack4<T>::store(out + i * 4, v[0] * scale + 0.f, v[1] * scale + 0.f, v[2] * scale + 0.f, v[3] * scale + 0.f);
   }
 }
 

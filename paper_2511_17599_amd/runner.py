@@ -58,6 +58,17 @@ class Session:
         return B.flce_backward(self.H, self.W, self.y, self.lse, self.N, self.d, self.V, self.ignore_index, self.red,
                                self.dt, self.grad_loss, self.dH, self.dW, self.ws, self.bwd_bytes, self.stream())
 
+    def forward_with_grads(self):
+        """Alg. 3: loss, lse and the unscaled gradients (left in dH, dW)."""
+        return B.flce_forward_with_grads(self.H, self.W, self.y, self.N, self.d, self.V, self.ignore_index, self.red,
+                                         self.dt, self.loss, self.lse, self.dH, self.dW, self.ws, self.ws.numel(),
+                                         self.stream())
+
+    def scale(self):
+        """Alg. 4: dH, dW scaled in place by the upstream gradient."""
+        return B.flce_scale(self.dH, self.dW, self.N, self.d, self.V, self.red, self.dt, self.grad_loss, self.ws,
+                            self.dH, self.dW, self.stream())
+
     def device_status(self):
         return B.flce_last_device_status(self.ws, self.stream())
 

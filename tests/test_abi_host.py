@@ -72,3 +72,14 @@ def test_bad_arguments_are_rejected_without_a_device():
     assert b(dW=None) == B.FLCE_ERR_BAD_ARG
     assert b(wsb=need_b - 1) == B.FLCE_ERR_WORKSPACE
     assert B.lib().flce_last_device_status(None, None, None) == B.FLCE_ERR_BAD_ARG
+    # Alg. 3 / Alg. 4 entry points: one workspace that serves both halves, no NULL tensors
+    g = lambda **kw: B.flce_forward_with_grads(p, p, p, 256, 64, 512, -100, B.FLCE_REDUCE_MEAN, B.FLCE_DTYPE_F32, p, p,
+                                               kw.get("dH", p), p, p, kw.get("wsb", max(need_f, need_b)))
+    assert g(dH=None) == B.FLCE_ERR_BAD_ARG
+    assert g(wsb=max(need_f, need_b) - 1) == B.FLCE_ERR_WORKSPACE
+    sc = lambda **kw: B.flce_scale(p, kw.get("dWp", p), 256, kw.get("d", 64), 512, kw.get("red", B.FLCE_REDUCE_MEAN),
+                                   B.FLCE_DTYPE_F32, 1.0, kw.get("ws", p), p, p)
+    assert sc(dWp=None) == B.FLCE_ERR_BAD_ARG
+    assert sc(ws=None) == B.FLCE_ERR_BAD_ARG
+    assert sc(red=5) == B.FLCE_ERR_BAD_ARG
+    assert sc(d=63) == B.FLCE_ERR_BAD_SHAPE

@@ -206,3 +206,49 @@ def test_largest_staging_tile():
     rows reaches the end of what one buffer descriptor can address."""
     wl = custom("g_2gib", 32728, 64, 32750, "bf16", 71, ignore_frac=0.003)
     check_against_oracle(wl, I.make_inputs(wl))
+
+
+@pytest.mark.parametrize("dtype,reduction,grad_loss", [("bf16", "mean", 1.0), ("bf16", "sum", -0.5), ("f32", "mean", 3.0)])
+def test_partial_gradients_then_scaling(dtype, reduction, grad_loss):
+    """Alg. 3 (loss + gradients without the upstream gradient) and Alg. 4 (scaling) through their own
+    entry points, against the two-stage oracle: the partial gradients are the gradients of the summed
+    loss, the scaled ones those of the requested reduction."""
+    wl = custom(f"alg3_{dtype}_{reduction}", 700, 160, 1500, dtype, 81, ignore_frac=0.1, reduction=reduction)
+    x = I.make_inputs(wl)
+    print(f"[case] {wl.name} partial gradients + scaling", flush=True)
+    from paper_2511_17599_amd.runner import session_for, to_host_f64
+    s = session_for(wl, x, grad_loss=grad_loss)
+    assert s.forward_with_grads() == B.FLCE_OK
+    st, nv = s.device_status()
+    Hd, Wd = I.to_f64(x["H"]), I.to_f64(x["W"])
+    f = O.forward(Hd, Wd, x["y"], wl.ignore_index, wl.reduction)
+    part = O.backward(Hd, Wd, x["y"], wl.ignore_index, "sum", 1.0)
+    full = O.backward(Hd, Wd, x["y"], wl.ignore_index, wl.reduction, grad_loss)
+    tol = TOL[dtype]
+    assert st == B.FLCE_OK and nv == f["n_valid"]
+    assert abs(float(s.loss.item()) - f["loss"]) <= tol["loss"] * abs(f["loss"])
+    assert np.abs(to_host_f64(s.lse) - f["lse"]).max() <= tol["lse"] * np.abs(f["lse"]).max()
+    assert nerr(to_host_f64(s.dH), part["dH"]) <= tol["grad"]
+    assert nerr(to_host_f64(s.dW), part["dW"]) <= tol["grad"]
+    assert s.scale() == B.FLCE_OK
+    assert nerr(to_host_f64(s.dH), full["dH"]) <= tol["grad"]
+    assert nerr(to_host_f64(s.dW), full["dW"]) <= tol["grad"]
+    raw = s.dH.view(torch.int16 if dtype == "bf16" else torch.int32).cpu().numpy()
+    assert not raw[~f["valid"]].any()                      # rows that do not count stay exactly +0
+
+
+def test_partial_gradients_against_streaming_algorithms():
+    """A case small enough for the per-row, per-vocabulary-entry loops of Alg. 3 and Alg. 4 as stated."""
+    from oracle import streaming as S
+    from paper_2511_17599_amd.runner import session_for, to_host_f64
+    wl = custom("alg3_stream", 7, 8, 37, "f32", 82)
+    x = I.make_inputs(wl)
+    s = session_for(wl, x, grad_loss=2.5)
+    assert s.forward_with_grads() == B.FLCE_OK
+    Hd, Wd = I.to_f64(x["H"]), I.to_f64(x["W"])
+    loss, dHp, dWp, m, a = S.alg3_forward_partial(Hd, Wd, x["y"])
+    assert abs(float(s.loss.item()) - loss) <= 1e-5 * abs(loss)           # Alg. 1 ends with the division by B*T
+    assert nerr(to_host_f64(s.dH), dHp) <= 1e-4 and nerr(to_host_f64(s.dW), dWp) <= 1e-4
+    assert s.scale() == B.FLCE_OK
+    dH, dW = S.alg4_scale(dHp, dWp, 2.5 / wl.N)
+    assert nerr(to_host_f64(s.dH), dH) <= 1e-4 and nerr(to_host_f64(s.dW), dW) <= 1e-4
