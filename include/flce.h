@@ -143,6 +143,49 @@ flce_status flce_scale(const void* dH_partial, const void* dW_partial,
                        const void* workspace, void* dH_out, void* dW_out, void* hip_stream);
 
 /*
+ * Vocabulary-sliced calls (Section "Model Parallelism", tensor parallelism: the outer loop restricted to
+ * the local weight slice, partial results aggregated afterwards).  A slice is the V_slice vocabulary
+ * rows [v_begin, v_begin + V_slice) of V_total, given as W_slice[V_slice][d]; targets stay global ids.
+ * One GPU can run the slices one after another; across GPUs the (m, a, z_target) arrays and the partial
+ * dH are what the ranks exchange (this library does not communicate).
+ *
+ * flce_forward_partial: per row i, over the slice only,
+ *     m_out[i] = max_v Z_iv,  a_out[i] = sum_v exp(Z_iv - m_out[i]),
+ *     zt_out[i] = Z_{i,y_i} if y_i lies in the slice and the row counts, else 0.
+ *   (Alg. 1's state after the slice's part of the vocabulary loop; N floats each, device.)
+ *   workspace: flce_workspace_bytes(N, d, V_slice, dt, 0).  Writes no status header.
+ *
+ * flce_merge_partials: merges n_parts such triples in part order (part k of row i at index k*N + i of
+ *   each array) into lse_out[N] and the mean or sum loss over the counted rows, exactly as the
+ *   forward's own epilogue merges its windows (Section "Window-based Strategy").  Counted = target
+ *   not ignore_index and inside [0, V_total); the workspace (flce_merge_workspace_bytes(N) bytes,
+ *   256-byte aligned) receives the status header read by flce_last_device_status.
+ *
+ * flce_backward_partial: Alg. 2 restricted to the slice, with the GLOBAL lse:
+ *     dW_slice_out[V_slice][d] = the rows [v_begin, v_begin + V_slice) of dW, complete;
+ *     dH_partial_out[N][d]     = sum over the slice's v of G_iv W_v; dH is the sum of these over all slices
+ *                                (rounded to dt per slice; rows that do not count are +0).
+ *   Gamma = grad_loss / n_valid (mean) or grad_loss (sum), n_valid counted over all rows as above.
+ *   workspace: flce_workspace_bytes(N, d, V_slice, dt, 1).
+ * Errors as for flce_forward / flce_backward; FLCE_ERR_BAD_SHAPE also when the slice is not inside [0, V_total).
+ */
+flce_status flce_forward_partial(const void* H, const void* W_slice, const int64_t* targets,
+                                 int64_t N, int64_t d, int64_t V_slice, int64_t v_begin, int64_t V_total,
+                                 int64_t ignore_index, flce_dtype dt,
+                                 float* m_out, float* a_out, float* zt_out,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+size_t flce_merge_workspace_bytes(int64_t N);
+flce_status flce_merge_partials(const float* m_parts, const float* a_parts, const float* zt_parts, int n_parts,
+                                const int64_t* targets, int64_t N, int64_t V_total, int64_t ignore_index,
+                                flce_reduction reduction, float* loss_out, float* lse_out,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+flce_status flce_backward_partial(const void* H, const void* W_slice, const int64_t* targets, const float* lse,
+                                  int64_t N, int64_t d, int64_t V_slice, int64_t v_begin, int64_t V_total,
+                                  int64_t ignore_index, flce_reduction reduction, flce_dtype dt, float grad_loss,
+                                  void* dH_partial_out, void* dW_slice_out,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Synchronises `hip_stream`, then reports what the last flce_forward or
  * flce_backward that used `workspace` latched on the device: FLCE_OK or
  * FLCE_ERR_TARGET_RANGE (FLCE_ERR_HIP if the synchronisation or copy fails).

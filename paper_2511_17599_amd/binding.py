@@ -19,7 +19,8 @@ FLCE_DTYPE_BF16, FLCE_DTYPE_F32 = 0, 1
 FLCE_REDUCE_MEAN, FLCE_REDUCE_SUM = 0, 1
 
 EXPORTS = ("flce_version", "flce_status_string", "flce_workspace_bytes", "flce_forward", "flce_backward",
-           "flce_forward_with_grads", "flce_scale", "flce_last_device_status", "flce_profile_enable",
+           "flce_forward_with_grads", "flce_scale", "flce_forward_partial", "flce_merge_workspace_bytes",
+           "flce_merge_partials", "flce_backward_partial", "flce_last_device_status", "flce_profile_enable",
            "flce_profile_collect")
 PROF_CLASSES = ("fwd_tiles", "fwd_epilogue", "bwd_prep", "recompute", "contract_dW", "contract_dH", "scale")
 
@@ -54,6 +55,20 @@ def lib():
         L.flce_scale.restype = c.c_int
         L.flce_scale.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_int,
                                  c.c_float, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.flce_forward_partial.restype = c.c_int
+        L.flce_forward_partial.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
+                                           c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_void_p, c.c_void_p,
+                                           c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+        L.flce_merge_workspace_bytes.restype = c.c_size_t
+        L.flce_merge_workspace_bytes.argtypes = [c.c_int64]
+        L.flce_merge_partials.restype = c.c_int
+        L.flce_merge_partials.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int, c.c_void_p, c.c_int64,
+                                          c.c_int64, c.c_int64, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p,
+                                          c.c_size_t, c.c_void_p]
+        L.flce_backward_partial.restype = c.c_int
+        L.flce_backward_partial.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64,
+                                            c.c_int64, c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_int, c.c_float,
+                                            c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
         L.flce_last_device_status.restype = c.c_int
         L.flce_last_device_status.argtypes = [c.c_void_p, c.c_void_p, c.POINTER(c.c_int64)]
         L.flce_profile_enable.restype = c.c_int
@@ -115,6 +130,31 @@ def flce_forward_with_grads(H, W, targets, N, d, V, ignore_index, reduction, dt,
 def flce_scale(dH_partial, dW_partial, N, d, V, reduction, dt, grad_loss, workspace, dH_out, dW_out, hip_stream=None):
     return lib().flce_scale(_ptr(dH_partial), _ptr(dW_partial), N, d, V, reduction, dt, float(grad_loss),
                             _ptr(workspace), _ptr(dH_out), _ptr(dW_out), _stream(hip_stream))
+
+
+def flce_forward_partial(H, W_slice, targets, N, d, V_slice, v_begin, V_total, ignore_index, dt, m_out, a_out, zt_out,
+                         workspace, workspace_bytes, hip_stream=None):
+    return lib().flce_forward_partial(_ptr(H), _ptr(W_slice), _ptr(targets), N, d, V_slice, v_begin, V_total,
+                                      ignore_index, dt, _ptr(m_out), _ptr(a_out), _ptr(zt_out), _ptr(workspace),
+                                      workspace_bytes, _stream(hip_stream))
+
+
+def flce_merge_workspace_bytes(N):
+    return int(lib().flce_merge_workspace_bytes(N))
+
+
+def flce_merge_partials(m_parts, a_parts, zt_parts, n_parts, targets, N, V_total, ignore_index, reduction, loss_out,
+                        lse_out, workspace, workspace_bytes, hip_stream=None):
+    return lib().flce_merge_partials(_ptr(m_parts), _ptr(a_parts), _ptr(zt_parts), n_parts, _ptr(targets), N,
+                                     V_total, ignore_index, reduction, _ptr(loss_out), _ptr(lse_out),
+                                     _ptr(workspace), workspace_bytes, _stream(hip_stream))
+
+
+def flce_backward_partial(H, W_slice, targets, lse, N, d, V_slice, v_begin, V_total, ignore_index, reduction, dt,
+                          grad_loss, dH_partial_out, dW_slice_out, workspace, workspace_bytes, hip_stream=None):
+    return lib().flce_backward_partial(_ptr(H), _ptr(W_slice), _ptr(targets), _ptr(lse), N, d, V_slice, v_begin,
+                                       V_total, ignore_index, reduction, dt, float(grad_loss), _ptr(dH_partial_out),
+                                       _ptr(dW_slice_out), _ptr(workspace), workspace_bytes, _stream(hip_stream))
 
 
 def flce_last_device_status(workspace, hip_stream=None):

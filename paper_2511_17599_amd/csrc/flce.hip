@@ -198,9 +198,14 @@ hipError_t prepare_kernels() {
   return hipSuccess;
 }
 
+// W holds the p.V vocabulary rows [slice.v_begin, slice.v_begin + p.V) of slice.V_total.  With m_out set the
+// call stops after the window merge and hands out the slice's (m, a, z_target) per row.
+struct Slice { int64_t V_total, v_begin; };
+
 template <typename T, typename U, typename L>
 flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t* y, int64_t ignore_index,
-                      int mean, float* loss_out, float* lse_out, char* ws, hipStream_t st) {
+                      int mean, float* loss_out, float* lse_out, char* ws, hipStream_t st, Slice slice,
+                      float* m_out = nullptr, float* a_out = nullptr, float* zt_out = nullptr) {
   if (prepare_kernels<T, L>() != hipSuccess) return FLCE_ERR_HIP;
   Header* hdr = reinterpret_cast<Header*>(ws);
   float* part = reinterpret_cast<float*>(ws + p.off_part);
@@ -222,19 +227,24 @@ flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t
       ProfScope ps(FLCE_PROF_FWD_TILES, st);
       fwd_tiles_kernel<T, L, true><<<grid, L::THREADS, L::LDS, st>>>(
           static_cast<const T*>(H), HT, static_cast<const T*>(W), y, (int)p.N, (int)p.d, (int)p.V, ignore_index,
-          p.n_rb, p.n_win, p.n_vt, part);
+          slice.V_total, slice.v_begin, p.n_rb, p.n_win, p.n_vt, part);
     }
   } else {
     ProfScope ps(FLCE_PROF_FWD_TILES, st);
     fwd_tiles_kernel<T, L, false><<<grid, L::THREADS, L::LDS, st>>>(
         static_cast<const T*>(H), nullptr, static_cast<const T*>(W), y, (int)p.N, (int)p.d, (int)p.V, ignore_index,
-        p.n_rb, p.n_win, p.n_vt, part);
+        slice.V_total, slice.v_begin, p.n_rb, p.n_win, p.n_vt, part);
   }
   {
     ProfScope ps(FLCE_PROF_FWD_EPILOGUE, st);
-    merge_rows_kernel<<<p.n_rb, 256, 0, st>>>(part, p.n_win, p.npad, y, (int)p.N, (int)p.V, ignore_index, lse_out,
-                                              blk_loss, blk_cnt, blk_oor);
-    finalize_loss_kernel<<<1, 256, 0, st>>>(blk_loss, blk_cnt, blk_oor, p.n_rb, mean, hdr, loss_out);
+    if (m_out) {
+      merge_rows_partial_kernel<<<p.n_rb, 256, 0, st>>>(part, p.n_win, p.npad, (int)p.N, m_out, a_out, zt_out);
+    } else {
+      const int64_t plane = (int64_t)p.n_win * p.npad;
+      merge_rows_kernel<<<p.n_rb, 256, 0, st>>>(part, part + plane, part + 2 * plane, p.n_win, p.npad, y, (int)p.N,
+                                                slice.V_total, ignore_index, lse_out, blk_loss, blk_cnt, blk_oor);
+      finalize_loss_kernel<<<1, 256, 0, st>>>(blk_loss, blk_cnt, blk_oor, p.n_rb, mean, hdr, loss_out);
+    }
   }
   return hipGetLastError() == hipSuccess ? FLCE_OK : FLCE_ERR_HIP;
 }
@@ -242,7 +252,7 @@ flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t
 template <typename T, typename U, typename L>
 flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_t* y, const float* lse,
                        int64_t ignore_index, int mean, float grad_loss, void* dH, void* dW, char* ws,
-                       hipStream_t st) {
+                       hipStream_t st, Slice slice) {
   if (prepare_kernels<T, L>() != hipSuccess) return FLCE_ERR_HIP;
   const int N = (int)p.N, d = (int)p.d, V = (int)p.V;
   Header* hdr = reinterpret_cast<Header*>(ws);
@@ -263,10 +273,11 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
 
   {
     ProfScope ps(FLCE_PROF_BWD_PREP, st);
-    compact_targets_kernel<<<1, 1024, 0, st>>>(y, N, V, ignore_index, npad, rowmap, tgt_c, hdr);
+    compact_targets_kernel<<<1, 1024, 0, st>>>(y, N, V, slice.V_total, slice.v_begin, ignore_index, npad, rowmap,
+                                               tgt_c, hdr);
     gather_rows_kernel<<<npad, 256, 0, st>>>(static_cast<const char*>(H), row_bytes, rowmap, lse,
                                              reinterpret_cast<char*>(Hc), lse_c);
-    zero_uncounted_rows_kernel<<<N, 256, 0, st>>>(y, V, ignore_index, static_cast<char*>(dH), row_bytes);
+    zero_uncounted_rows_kernel<<<N, 256, 0, st>>>(y, slice.V_total, ignore_index, static_cast<char*>(dH), row_bytes);
     if (!L::TRANSPOSING || p.hkr) {
       // Hc^T [d][npad]: the dW contraction's K-contiguous operand (generic loop), or the recompute's
       // operand read across memory rows (tuned loop)
@@ -406,14 +417,18 @@ size_t flce_workspace_bytes(int64_t N, int64_t d, int64_t V, flce_dtype dt, int 
   return (size_t)(for_backward ? p.bwd_bytes : p.fwd_bytes);
 }
 
-flce_status flce_forward(const void* H, const void* W, const int64_t* targets, int64_t N, int64_t d, int64_t V,
-                         int64_t ignore_index, flce_reduction reduction, flce_dtype dt, float* loss_out,
-                         float* lse_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  if (!H || !W || !targets || !loss_out || !lse_out) return FLCE_ERR_BAD_ARG;
+static flce_status forward_impl(const void* H, const void* W, const int64_t* targets, int64_t N, int64_t d,
+                                int64_t V, int64_t ignore_index, flce_reduction reduction, flce_dtype dt,
+                                float* loss_out, float* lse_out, void* workspace, size_t workspace_bytes,
+                                void* hip_stream, flce::Slice slice, float* m_out, float* a_out, float* zt_out) {
+  const bool partial = m_out || a_out || zt_out;
+  if (!H || !W || !targets) return FLCE_ERR_BAD_ARG;
+  if (partial ? (!m_out || !a_out || !zt_out) : (!loss_out || !lse_out)) return FLCE_ERR_BAD_ARG;
   if (reduction != FLCE_REDUCE_MEAN && reduction != FLCE_REDUCE_SUM) return FLCE_ERR_BAD_ARG;
   if (dt != FLCE_DTYPE_BF16 && dt != FLCE_DTYPE_F32) return FLCE_ERR_BAD_ARG;
   flce::Plan p;
   if (!flce::make_plan(N, d, V, dt, p)) return FLCE_ERR_BAD_SHAPE;
+  if (slice.v_begin < 0 || slice.v_begin + V > slice.V_total) return FLCE_ERR_BAD_SHAPE;
   if (!flce::aligned16(H) || !flce::aligned16(W)) return FLCE_ERR_BAD_ARG;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < (size_t)p.fwd_bytes)
     return FLCE_ERR_WORKSPACE;
@@ -423,23 +438,24 @@ flce_status flce_forward(const void* H, const void* W, const int64_t* targets, i
   if (dt == FLCE_DTYPE_BF16) {
     if (p.fast)
       return flce::forward_t<flce::bf16_t, uint16_t, flce::FastLoop>(p, H, W, targets, ignore_index, mean, loss_out,
-                                                                     lse_out, ws, st);
-    return flce::forward_t<flce::bf16_t, uint16_t, flce::GenericLoop<flce::bf16_t>>(p, H, W, targets, ignore_index,
-                                                                                    mean, loss_out, lse_out, ws, st);
+                                                                     lse_out, ws, st, slice, m_out, a_out, zt_out);
+    return flce::forward_t<flce::bf16_t, uint16_t, flce::GenericLoop<flce::bf16_t>>(
+        p, H, W, targets, ignore_index, mean, loss_out, lse_out, ws, st, slice, m_out, a_out, zt_out);
   }
   return flce::forward_t<float, uint32_t, flce::GenericLoop<float>>(p, H, W, targets, ignore_index, mean, loss_out,
-                                                                    lse_out, ws, st);
+                                                                    lse_out, ws, st, slice, m_out, a_out, zt_out);
 }
 
-flce_status flce_backward(const void* H, const void* W, const int64_t* targets, const float* lse, int64_t N,
-                          int64_t d, int64_t V, int64_t ignore_index, flce_reduction reduction, flce_dtype dt,
-                          float grad_loss, void* dH_out, void* dW_out, void* workspace, size_t workspace_bytes,
-                          void* hip_stream) {
+static flce_status backward_impl(const void* H, const void* W, const int64_t* targets, const float* lse, int64_t N,
+                                 int64_t d, int64_t V, int64_t ignore_index, flce_reduction reduction, flce_dtype dt,
+                                 float grad_loss, void* dH_out, void* dW_out, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream, flce::Slice slice) {
   if (!H || !W || !targets || !lse || !dH_out || !dW_out) return FLCE_ERR_BAD_ARG;
   if (reduction != FLCE_REDUCE_MEAN && reduction != FLCE_REDUCE_SUM) return FLCE_ERR_BAD_ARG;
   if (dt != FLCE_DTYPE_BF16 && dt != FLCE_DTYPE_F32) return FLCE_ERR_BAD_ARG;
   flce::Plan p;
   if (!flce::make_plan(N, d, V, dt, p)) return FLCE_ERR_BAD_SHAPE;
+  if (slice.v_begin < 0 || slice.v_begin + V > slice.V_total) return FLCE_ERR_BAD_SHAPE;
   if (!flce::aligned16(H) || !flce::aligned16(W) || !flce::aligned16(dH_out) || !flce::aligned16(dW_out))
     return FLCE_ERR_BAD_ARG;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < (size_t)p.bwd_bytes)
@@ -450,12 +466,78 @@ flce_status flce_backward(const void* H, const void* W, const int64_t* targets, 
   if (dt == FLCE_DTYPE_BF16) {
     if (p.fast)
       return flce::backward_t<flce::bf16_t, uint16_t, flce::FastLoop>(p, H, W, targets, lse, ignore_index, mean,
-                                                                      grad_loss, dH_out, dW_out, ws, st);
+                                                                      grad_loss, dH_out, dW_out, ws, st, slice);
     return flce::backward_t<flce::bf16_t, uint16_t, flce::GenericLoop<flce::bf16_t>>(
-        p, H, W, targets, lse, ignore_index, mean, grad_loss, dH_out, dW_out, ws, st);
+        p, H, W, targets, lse, ignore_index, mean, grad_loss, dH_out, dW_out, ws, st, slice);
   }
   return flce::backward_t<float, uint32_t, flce::GenericLoop<float>>(p, H, W, targets, lse, ignore_index, mean,
-                                                                     grad_loss, dH_out, dW_out, ws, st);
+                                                                     grad_loss, dH_out, dW_out, ws, st, slice);
+}
+
+flce_status flce_forward(const void* H, const void* W, const int64_t* targets, int64_t N, int64_t d, int64_t V,
+                         int64_t ignore_index, flce_reduction reduction, flce_dtype dt, float* loss_out,
+                         float* lse_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return forward_impl(H, W, targets, N, d, V, ignore_index, reduction, dt, loss_out, lse_out, workspace,
+                      workspace_bytes, hip_stream, flce::Slice{V, 0}, nullptr, nullptr, nullptr);
+}
+
+flce_status flce_backward(const void* H, const void* W, const int64_t* targets, const float* lse, int64_t N,
+                          int64_t d, int64_t V, int64_t ignore_index, flce_reduction reduction, flce_dtype dt,
+                          float grad_loss, void* dH_out, void* dW_out, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  return backward_impl(H, W, targets, lse, N, d, V, ignore_index, reduction, dt, grad_loss, dH_out, dW_out,
+                       workspace, workspace_bytes, hip_stream, flce::Slice{V, 0});
+}
+
+flce_status flce_forward_partial(const void* H, const void* W_slice, const int64_t* targets, int64_t N, int64_t d,
+                                 int64_t V_slice, int64_t v_begin, int64_t V_total, int64_t ignore_index,
+                                 flce_dtype dt, float* m_out, float* a_out, float* zt_out, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  if (!m_out || !a_out || !zt_out) return FLCE_ERR_BAD_ARG;
+  return forward_impl(H, W_slice, targets, N, d, V_slice, ignore_index, FLCE_REDUCE_SUM, dt, nullptr, nullptr,
+                      workspace, workspace_bytes, hip_stream, flce::Slice{V_total, v_begin}, m_out, a_out, zt_out);
+}
+
+size_t flce_merge_workspace_bytes(int64_t N) {
+  if (N <= 0 || N > 0x7FFFFF00ll) return 0;
+  const int64_t n_rb = flce::ceil_div(N, flce::TILE);
+  return (size_t)(flce::ALIGN + 3 * flce::align_up(n_rb * 4, flce::ALIGN));
+}
+
+flce_status flce_merge_partials(const float* m_parts, const float* a_parts, const float* zt_parts, int n_parts,
+                                const int64_t* targets, int64_t N, int64_t V_total, int64_t ignore_index,
+                                flce_reduction reduction, float* loss_out, float* lse_out, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+  if (!m_parts || !a_parts || !zt_parts || !targets || !loss_out || !lse_out || n_parts < 1) return FLCE_ERR_BAD_ARG;
+  if (reduction != FLCE_REDUCE_MEAN && reduction != FLCE_REDUCE_SUM) return FLCE_ERR_BAD_ARG;
+  const size_t need = flce_merge_workspace_bytes(N);
+  if (need == 0 || V_total <= 0) return FLCE_ERR_BAD_SHAPE;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
+    return FLCE_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  const int n_rb = (int)flce::ceil_div(N, flce::TILE);
+  const int64_t blk = flce::align_up((int64_t)n_rb * 4, flce::ALIGN);
+  flce::Header* hdr = reinterpret_cast<flce::Header*>(ws);
+  float* blk_loss = reinterpret_cast<float*>(ws + flce::ALIGN);
+  int* blk_cnt = reinterpret_cast<int*>(ws + flce::ALIGN + blk);
+  int* blk_oor = reinterpret_cast<int*>(ws + flce::ALIGN + 2 * blk);
+  flce::ProfScope ps(FLCE_PROF_FWD_EPILOGUE, st);
+  flce::merge_rows_kernel<<<n_rb, 256, 0, st>>>(m_parts, a_parts, zt_parts, n_parts, N, targets, (int)N, V_total,
+                                                ignore_index, lse_out, blk_loss, blk_cnt, blk_oor);
+  flce::finalize_loss_kernel<<<1, 256, 0, st>>>(blk_loss, blk_cnt, blk_oor, n_rb, reduction == FLCE_REDUCE_MEAN, hdr,
+                                                loss_out);
+  return hipGetLastError() == hipSuccess ? FLCE_OK : FLCE_ERR_HIP;
+}
+
+flce_status flce_backward_partial(const void* H, const void* W_slice, const int64_t* targets, const float* lse,
+                                  int64_t N, int64_t d, int64_t V_slice, int64_t v_begin, int64_t V_total,
+                                  int64_t ignore_index, flce_reduction reduction, flce_dtype dt, float grad_loss,
+                                  void* dH_partial_out, void* dW_slice_out, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+  return backward_impl(H, W_slice, targets, lse, N, d, V_slice, ignore_index, reduction, dt, grad_loss,
+                       dH_partial_out, dW_slice_out, workspace, workspace_bytes, hip_stream,
+                       flce::Slice{V_total, v_begin});
 }
 
 flce_status flce_forward_with_grads(const void* H, const void* W, const int64_t* targets, int64_t N, int64_t d,

@@ -86,13 +86,23 @@ struct Header {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Classifies one target: returns its id when the row counts, -1 otherwise, and
-// reports a counted id outside [0, V) through `oor`.
-__device__ __forceinline__ int classify_target(int64_t y, int64_t ignore_index, int V, bool& oor) {
+// Whether a row counts towards the loss: its target is not the ignore index and lies in
+// [0, V_total); a target outside that range that is not the ignore index is reported through `oor`.
+__device__ __forceinline__ bool target_counts(int64_t y, int64_t ignore_index, int64_t V_total, bool& oor) {
   oor = false;
-  if (y == ignore_index) return -1;
-  if (y < 0 || y >= (int64_t)V) { oor = true; return -1; }
-  return (int)y;
+  if (y == ignore_index) return false;
+  if (y < 0 || y >= V_total) { oor = true; return false; }
+  return true;
+}
+
+// A counted target as a column of the vocabulary slice [v_begin, v_begin + Vs) that a call works
+// on: its column inside the slice, or `outside` when it lies in another slice; -1 for rows that do
+// not count.  The whole vocabulary as the slice is v_begin = 0, Vs = V_total.
+__device__ __forceinline__ int classify_target_in_slice(int64_t y, int64_t ignore_index, int64_t V_total,
+                                                        int64_t v_begin, int Vs, int outside, bool& oor) {
+  if (!target_counts(y, ignore_index, V_total, oor)) return -1;
+  const int64_t c = y - v_begin;
+  return (c >= 0 && c < (int64_t)Vs) ? (int)c : outside;
 }
 
 // Merge of safe-softmax partials (m_k, a_k) in slot order; slots with a == 0 are
@@ -119,7 +129,8 @@ __device__ __forceinline__ void merge_fixed(const float (&m)[S], const float (&a
 template <typename T, typename L, bool HKR>
 __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
     const T* __restrict__ H, const T* __restrict__ HT, const T* __restrict__ W, const int64_t* __restrict__ y,
-    int N, int d, int V, int64_t ignore_index, int n_rb, int n_win, int n_vt, float* __restrict__ part) {
+    int N, int d, int V, int64_t ignore_index, int64_t V_total, int64_t v_begin, int n_rb, int n_win, int n_vt,
+    float* __restrict__ part) {
   extern __shared__ __align__(16) char lds[];
   const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
   int rb, win;
@@ -135,7 +146,8 @@ __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
   for (int j = 0; j < L::WN; ++j) {
     const int n = n0 + L::tile_n(j);
     bool oor;
-    tgt[j] = (n < N) ? classify_target(y[n], ignore_index, V, oor) : -1;
+    // W holds the V vocabulary rows [v_begin, v_begin + V) of V_total; a target in another slice matches no column
+    tgt[j] = (n < N) ? classify_target_in_slice(y[n], ignore_index, V_total, v_begin, V, -1, oor) : -1;
     m[j] = NEG_INF; a[j] = 0.f; zt[j] = 0.f;
   }
 
@@ -233,33 +245,37 @@ __device__ __forceinline__ float block_sum_256(float v, float* sh) {
   return r;
 }
 
-// One thread per row: merge the window partials in window order, lse = M + ln A,
-// loss_i = lse - z_target for counted rows; per-block sums in a fixed tree.
+// One thread per row: merge the partials (m, a, z_target) of `n_parts` windows or vocabulary
+// slices in their order (part k of row n at pm[k * stride + n], likewise pa, pz).
+__device__ __forceinline__ void merge_parts_of_row(const float* __restrict__ pm, const float* __restrict__ pa,
+                                                   const float* __restrict__ pz, int n_parts, int64_t stride, int n,
+                                                   float& M, float& A, float& z) {
+  M = NEG_INF;
+  for (int w = 0; w < n_parts; ++w)
+    if (pa[(int64_t)w * stride + n] > 0.f) M = fmaxf(M, pm[(int64_t)w * stride + n]);
+  A = 0.f; z = 0.f;
+  for (int w = 0; w < n_parts; ++w) {
+    const float mw = pm[(int64_t)w * stride + n], aw = pa[(int64_t)w * stride + n];
+    if (aw > 0.f) A += aw * fast_exp2((mw - M) * LOG2E);
+    z += pz[(int64_t)w * stride + n];
+  }
+}
+
+// lse = M + ln A, loss_i = lse - z_target for counted rows; per-block sums in a fixed tree.
 __global__ __launch_bounds__(256) void merge_rows_kernel(
-    const float* __restrict__ part, int n_win, int64_t npad, const int64_t* __restrict__ y, int N, int V,
-    int64_t ignore_index, float* __restrict__ lse_out, float* __restrict__ blk_loss, int* __restrict__ blk_cnt,
-    int* __restrict__ blk_oor) {
+    const float* __restrict__ pm, const float* __restrict__ pa, const float* __restrict__ pz, int n_parts,
+    int64_t stride, const int64_t* __restrict__ y, int N, int64_t V_total, int64_t ignore_index,
+    float* __restrict__ lse_out, float* __restrict__ blk_loss, int* __restrict__ blk_cnt, int* __restrict__ blk_oor) {
   __shared__ float sh[256];
   const int n = blockIdx.x * 256 + threadIdx.x;
   float loss = 0.f, cnt = 0.f, bad = 0.f;
   if (n < N) {
-    float M = NEG_INF;
-    for (int w = 0; w < n_win; ++w) {
-      const float aw = part[(int64_t)n_win * npad + (int64_t)w * npad + n];
-      if (aw > 0.f) M = fmaxf(M, part[(int64_t)w * npad + n]);
-    }
-    float A = 0.f, z = 0.f;
-    for (int w = 0; w < n_win; ++w) {
-      const float mw = part[(int64_t)w * npad + n];
-      const float aw = part[(int64_t)n_win * npad + (int64_t)w * npad + n];
-      if (aw > 0.f) A += aw * fast_exp2((mw - M) * LOG2E);
-      z += part[2 * (int64_t)n_win * npad + (int64_t)w * npad + n];
-    }
+    float M, A, z;
+    merge_parts_of_row(pm, pa, pz, n_parts, stride, n, M, A, z);
     const float lse = M + logf(A);
     lse_out[n] = lse;
     bool oor;
-    const int t = classify_target(y[n], ignore_index, V, oor);
-    if (t >= 0) { loss = lse - z; cnt = 1.f; }
+    if (target_counts(y[n], ignore_index, V_total, oor)) { loss = lse - z; cnt = 1.f; }
     if (oor) bad = 1.f;
   }
   const float bl = block_sum_256(loss, sh);
@@ -270,6 +286,19 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(
     blk_cnt[blockIdx.x] = (int)bc;
     blk_oor[blockIdx.x] = bb > 0.f ? 1 : 0;
   }
+}
+
+// The window merge of a call that covers one vocabulary slice: the slice's (m, a, z_target) per row,
+// to be merged with the other slices' later (Section 3.3, tensor parallelism).
+__global__ __launch_bounds__(256) void merge_rows_partial_kernel(const float* __restrict__ part, int n_win,
+                                                                 int64_t npad, int N, float* __restrict__ m_out,
+                                                                 float* __restrict__ a_out,
+                                                                 float* __restrict__ zt_out) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  float M, A, z;
+  merge_parts_of_row(part, part + (int64_t)n_win * npad, part + 2 * (int64_t)n_win * npad, n_win, npad, n, M, A, z);
+  m_out[n] = M; a_out[n] = A; zt_out[n] = z;
 }
 
 // One block: fixed-order fp64 sum of the per-block partials, normalisation, header.
@@ -309,10 +338,12 @@ __global__ __launch_bounds__(256) void finalize_loss_kernel(
 // compaction map.  Rows that do not count have an all-zero row of G, so the three
 // backward contractions run on the counted rows only, packed in ascending row order:
 //   rowmap[c] = original row of compact row c   (c < n_valid),  -1 for c >= n_valid
-//   tgt_c[c]  = its target id,                                   -1 for c >= n_valid
+//   tgt_c[c]  = its target's column in the vocabulary slice W holds (2^31 - 1, which matches no column,
+//               when the target lies in another slice),           -1 for c >= n_valid
 // One block; every thread owns a contiguous range of rows, an exclusive scan of the
 // per-thread counts gives each range its first compact index.
 __global__ __launch_bounds__(1024) void compact_targets_kernel(const int64_t* __restrict__ y, int N, int V,
+                                                               int64_t V_total, int64_t v_begin,
                                                                int64_t ignore_index, int npad,
                                                                int* __restrict__ rowmap, int* __restrict__ tgt_c,
                                                                Header* __restrict__ hdr) {
@@ -324,7 +355,7 @@ __global__ __launch_bounds__(1024) void compact_targets_kernel(const int64_t* __
   int c = 0, o = 0;
   for (int n = r0; n < r1; ++n) {
     bool oor;
-    if (classify_target(y[n], ignore_index, V, oor) >= 0) ++c;
+    if (classify_target_in_slice(y[n], ignore_index, V_total, v_begin, V, 0x7FFFFFFF, oor) >= 0) ++c;
     o |= oor ? 1 : 0;
   }
   sc[t] = c; so[t] = o;
@@ -340,7 +371,7 @@ __global__ __launch_bounds__(1024) void compact_targets_kernel(const int64_t* __
   int pos = sc[t] - c;                                 // exclusive prefix
   for (int n = r0; n < r1; ++n) {
     bool oor;
-    const int tg = classify_target(y[n], ignore_index, V, oor);
+    const int tg = classify_target_in_slice(y[n], ignore_index, V_total, v_begin, V, 0x7FFFFFFF, oor);
     if (tg >= 0) { rowmap[pos] = n; tgt_c[pos] = tg; ++pos; }
   }
   for (int cidx = total + t; cidx < npad; cidx += 1024) { rowmap[cidx] = -1; tgt_c[cidx] = -1; }
@@ -370,12 +401,12 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict
 }
 
 // dH rows of tokens that do not count are exactly +0.  One block per row.
-__global__ __launch_bounds__(256) void zero_uncounted_rows_kernel(const int64_t* __restrict__ y, int V,
+__global__ __launch_bounds__(256) void zero_uncounted_rows_kernel(const int64_t* __restrict__ y, int64_t V_total,
                                                                   int64_t ignore_index, char* __restrict__ dH,
                                                                   int64_t row_bytes) {
   const int n = blockIdx.x;
   bool oor;
-  if (classify_target(y[n], ignore_index, V, oor) >= 0) return;
+  if (target_counts(y[n], ignore_index, V_total, oor)) return;
   const u32x4 z = {0u, 0u, 0u, 0u};
   u32x4* dst = reinterpret_cast<u32x4*>(dH + (int64_t)n * row_bytes);
   const int nvec = (int)(row_bytes / 16);

@@ -83,3 +83,23 @@ def test_bad_arguments_are_rejected_without_a_device():
     assert sc(ws=None) == B.FLCE_ERR_BAD_ARG
     assert sc(red=5) == B.FLCE_ERR_BAD_ARG
     assert sc(d=63) == B.FLCE_ERR_BAD_SHAPE
+    # vocabulary-sliced calls: the slice must lie inside [0, V_total); the merge needs its own small workspace
+    fp = lambda **kw: B.flce_forward_partial(p, p, p, 256, 64, kw.get("Vs", 128), kw.get("v0", 384), 512, -100,
+                                             B.FLCE_DTYPE_F32, kw.get("m", p), p, p, p, kw.get("wsb", need_f))
+    assert fp(v0=385) == B.FLCE_ERR_BAD_SHAPE
+    assert fp(v0=-1) == B.FLCE_ERR_BAD_SHAPE
+    assert fp(m=None) == B.FLCE_ERR_BAD_ARG
+    assert fp(wsb=16) == B.FLCE_ERR_WORKSPACE
+    need_m = B.flce_merge_workspace_bytes(256)
+    assert 0 < need_m <= 4096 and B.flce_merge_workspace_bytes(0) == 0
+    mp = lambda **kw: B.flce_merge_partials(p, kw.get("a", p), p, kw.get("n", 2), p, 256, 512, -100,
+                                            B.FLCE_REDUCE_MEAN, p, p, p, kw.get("wsb", need_m))
+    assert mp(a=None) == B.FLCE_ERR_BAD_ARG
+    assert mp(n=0) == B.FLCE_ERR_BAD_ARG
+    assert mp(wsb=need_m - 1) == B.FLCE_ERR_WORKSPACE
+    bp = lambda **kw: B.flce_backward_partial(p, p, p, p, 256, 64, 128, kw.get("v0", 0), kw.get("Vt", 512), -100,
+                                              B.FLCE_REDUCE_MEAN, B.FLCE_DTYPE_F32, 1.0, p, kw.get("dW", p), p,
+                                              kw.get("wsb", need_b))
+    assert bp(Vt=100) == B.FLCE_ERR_BAD_SHAPE
+    assert bp(dW=None) == B.FLCE_ERR_BAD_ARG
+    assert bp(wsb=16) == B.FLCE_ERR_WORKSPACE

@@ -252,3 +252,44 @@ def test_partial_gradients_against_streaming_algorithms():
     assert s.scale() == B.FLCE_OK
     dH, dW = S.alg4_scale(dHp, dWp, 2.5 / wl.N)
     assert nerr(to_host_f64(s.dH), dH) <= 1e-4 and nerr(to_host_f64(s.dW), dW) <= 1e-4
+
+
+@pytest.mark.parametrize("dtype,reduction", [("bf16", "mean"), ("f32", "sum")])
+def test_vocabulary_slices_merge_to_the_whole(dtype, reduction):
+    """The vocabulary cut into uneven slices (one exactly a tile, one a single row, ragged ends), each run through
+    the partial calls and merged: per slice (m, a, z_target) against their definitions, the merged loss / lse and
+    the assembled dW / summed dH against the two-stage oracle on the whole vocabulary."""
+    from paper_2511_17599_amd.runner import run_sliced
+    wl = custom(f"slices_{dtype}", 700, 160, 1500, dtype, 91, ignore_frac=0.1, reduction=reduction)
+    x = I.make_inputs(wl)
+    x["y"][5] = 1700                                         # one target outside the whole vocabulary
+    cuts = [0, 256, 257, 700, 1333, 1500]
+    print(f"[case] {wl.name} cuts {cuts}", flush=True)
+    got = run_sliced(wl, x, cuts, grad_loss=0.5)
+    Hd, Wd = I.to_f64(x["H"]), I.to_f64(x["W"])
+    f = O.forward(Hd, Wd, x["y"], wl.ignore_index, wl.reduction)
+    b = O.backward(Hd, Wd, x["y"], wl.ignore_index, wl.reduction, 0.5)
+    tol = TOL[dtype]
+    assert f["out_of_range"] and got["status"] == B.FLCE_ERR_TARGET_RANGE and got["n_valid"] == f["n_valid"]
+    Z = Hd @ Wd.T
+    for k in range(len(cuts) - 1):
+        v0, v1 = cuts[k], cuts[k + 1]
+        m, a, zt = got["parts"][:, k]
+        # (m, a) is one of many equal representations of the slice's log-sum-exp; m itself is its largest logit
+        lse_k = np.log(np.exp(Z[:, v0:v1] - Z[:, v0:v1].max(axis=1, keepdims=True)).sum(axis=1)) + Z[:, v0:v1].max(axis=1)
+        assert np.abs(m - Z[:, v0:v1].max(axis=1)).max() <= 1e-5 * np.abs(Z).max()
+        assert np.abs(m + np.log(a) - lse_k).max() <= tol["lse"] * np.abs(lse_k).max()
+        inside = f["valid"] & (x["y"] >= v0) & (x["y"] < v1)
+        want = np.where(inside, Z[np.arange(wl.N), np.clip(x["y"], 0, wl.V - 1)], 0.0)
+        assert np.abs(zt - want).max() <= 1e-5 * np.abs(Z).max()
+        assert not zt[~inside].any()                        # exactly 0 where the target is elsewhere
+    assert abs(got["loss"] - f["loss"]) <= tol["loss"] * abs(f["loss"])
+    assert np.abs(got["lse"] - f["lse"]).max() <= tol["lse"] * np.abs(f["lse"]).max()
+    assert nerr(got["dW"], b["dW"]) <= tol["grad"]
+    assert nerr(got["dH"], b["dH"]) <= tol["grad"]
+    for bits in got["dH_bits"]:
+        assert not bits[~f["valid"]].any()
+    # and against the unsliced call on the same device
+    whole = run_workload(wl, x, grad_loss=0.5)
+    assert np.abs(whole["lse"] - got["lse"]).max() <= 4e-6 * np.abs(f["lse"]).max()
+    assert nerr(whole["dW"], got["dW"]) <= (1e-2 if dtype == "bf16" else 1e-5)
