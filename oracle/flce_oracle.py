@@ -38,7 +38,8 @@ per-block G^T . H products.
 
 Every public function here is pinned by tests/test_oracle_pins.py (closed
 forms, invariants, finite differences, an independent scalar transcription of
-Alg. 1/2, and the fp64 log-softmax/NLL of two numerical libraries).
+Alg. 1/2, and the fp64 log-softmax/NLL of two numerical libraries; the
+label-smoothed per-row variant also by a library's own label-smoothed loss).
 """
 from __future__ import annotations
 
@@ -144,6 +145,71 @@ def backward(H, W, y, ignore_index=-100, reduction=MEAN, grad_loss=1.0, block_ro
         dH[r0:r1] = G @ W                              # Eq. 4
         dW += G.T @ H[r0:r1]                           # Eq. 5
     return dict(dH=dH, dW=dW, gamma=gam, n_valid=n_valid)
+
+
+# ---------------------------------------------------------------------------
+# Per-position upstream gradients and label smoothing.
+#
+# Alg. 2 takes an upstream gradient Gamma that may differ per position (the
+# non-scalar branch of Alg. 4 says the same); with one loss value per row
+# ("no reduction") that is the natural interface.  Label smoothing is the loss
+# variant the Discussion names.  The paper gives no formula for it; the reading
+# taken is the usual one: the target distribution of a counted row is
+#     q_v = (1 - eps) [v == y_i] + eps / V,
+#     loss_i = - sum_v q_v log softmax(Z_i)_v
+#            = (1 - eps) (lse_i - Z_{i,y_i}) + eps (lse_i - mean_v Z_iv),
+#     dloss_i / dZ_iv = softmax(Z_i)_v - q_v,
+# which is Eq. 2 and Appendix A.1 for eps = 0.
+# ---------------------------------------------------------------------------
+
+def forward_per_row(H, W, y, ignore_index=-100, label_smoothing=0.0, block_rows=1024):
+    """One loss value per row (0 for rows that do not count) and every row's
+    lse.  Returns a dict: loss_rows[N], lse[N], valid[N], n_valid, out_of_range."""
+    H, W = _f64(H), _f64(W)
+    N, V = H.shape[0], W.shape[0]
+    eps = float(label_smoothing)
+    y = np.asarray(y, dtype=np.int64)
+    valid, n_valid, oor = classify_targets(y, V, ignore_index)
+    lse = np.empty(N)
+    loss_rows = np.zeros(N)
+    for r0 in range(0, N, block_rows):
+        r1 = min(N, r0 + block_rows)
+        Z = H[r0:r1] @ W.T
+        mx = Z.max(axis=1)
+        lse[r0:r1] = mx + np.log(np.exp(Z - mx[:, None]).sum(axis=1))
+        logp = Z - lse[r0:r1, None]                    # log softmax, materialised
+        idx = np.nonzero(valid[r0:r1])[0]
+        nll = -logp[idx, y[r0:r1][idx]]
+        uniform = -logp[idx].mean(axis=1)
+        loss_rows[r0 + idx] = (1.0 - eps) * nll + eps * uniform
+    return dict(loss_rows=loss_rows, lse=lse, valid=valid, n_valid=n_valid, out_of_range=oor)
+
+
+def backward_per_row(H, W, y, grad_rows, ignore_index=-100, label_smoothing=0.0, block_rows=1024):
+    """Gradients of sum_i grad_rows[i] * loss_i: G_iv = grad_rows[i] * (softmax(Z_i)_v - q_v) on
+    counted rows, 0 elsewhere; dH = G . W (Eq. 4), dW = G^T . H (Eq. 5)."""
+    H, W = _f64(H), _f64(W)
+    N, V = H.shape[0], W.shape[0]
+    eps = float(label_smoothing)
+    y = np.asarray(y, dtype=np.int64)
+    gr = _f64(grad_rows)
+    valid, n_valid, _ = classify_targets(y, V, ignore_index)
+    dH = np.zeros_like(H)
+    dW = np.zeros_like(W)
+    for r0 in range(0, N, block_rows):
+        r1 = min(N, r0 + block_rows)
+        Z = H[r0:r1] @ W.T
+        mx = Z.max(axis=1, keepdims=True)
+        E = np.exp(Z - mx)
+        G = E / E.sum(axis=1, keepdims=True)
+        G -= eps / V
+        idx = np.nonzero(valid[r0:r1])[0]
+        G[idx, y[r0:r1][idx]] -= 1.0 - eps
+        G[~valid[r0:r1]] = 0.0
+        G *= gr[r0:r1, None]
+        dH[r0:r1] = G @ W
+        dW += G.T @ H[r0:r1]
+    return dict(dH=dH, dW=dW, n_valid=n_valid)
 
 
 # ---------------------------------------------------------------------------

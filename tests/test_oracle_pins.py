@@ -260,3 +260,87 @@ def test_sampled_entry_points_match_full():
     ids = np.array([0, 5, 39, int(y[y != IGN][0])])
     got = O.dW_rows(H, W[ids], ids, y, f["lse"], b["gamma"], IGN, V=40, block_rows=13)
     np.testing.assert_allclose(got, b["dW"][ids], atol=1e-15)
+
+
+# ---- P13: per-row upstream gradients and label smoothing ------------------
+def test_per_row_variant_reduces_to_the_scalar_one():
+    """eps = 0 and a constant upstream gradient are the mean / sum pipeline."""
+    H, W, y = rand_case(21, 19, 7, 23, n_ignored=4, w_std=1.0)
+    f = O.forward(H, W, y, IGN, "sum")
+    pr = O.forward_per_row(H, W, y, IGN, 0.0)
+    np.testing.assert_allclose(pr["loss_rows"], f["loss_rows"], rtol=1e-14, atol=1e-15)
+    np.testing.assert_allclose(pr["lse"], f["lse"], rtol=1e-15)
+    assert np.all(pr["loss_rows"][y == IGN] == 0.0)
+    b = O.backward(H, W, y, IGN, "mean", 0.7)
+    br = O.backward_per_row(H, W, y, np.full(len(y), 0.7 / f["n_valid"]), IGN, 0.0)
+    np.testing.assert_allclose(br["dH"], b["dH"], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(br["dW"], b["dW"], rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("eps", [0.0, 0.1, 0.35])
+def test_label_smoothing_closed_forms_and_invariants(eps):
+    N, d, V = 9, 6, 11
+    H, W, y = rand_case(22, N, d, V, n_ignored=2, w_std=1.0)
+    # W = 0: every log-probability is -ln V, so the loss is ln V whatever eps; G = 1/V - q
+    z = O.forward_per_row(H, np.zeros_like(W), y, IGN, eps)
+    np.testing.assert_allclose(z["loss_rows"][y != IGN], math.log(V), rtol=1e-15)
+    gr = np.linspace(0.5, 1.5, N)
+    b0 = O.backward_per_row(H, np.zeros_like(W), y, gr, IGN, eps)
+    assert np.abs(b0["dH"]).max() == 0.0
+    want = np.zeros((V, d))
+    for i in range(N):
+        if y[i] == IGN:
+            continue
+        q = np.full(V, eps / V)
+        q[y[i]] += 1.0 - eps
+        want += np.outer(gr[i] * (1.0 / V - q), H[i])
+    np.testing.assert_allclose(b0["dW"], want, rtol=0, atol=1e-15)
+    # rows of G sum to zero (p and q both sum to one): dW's column sums vanish, <dH,H> = <dW,W>
+    b = O.backward_per_row(H, W, y, gr, IGN, eps)
+    assert np.abs(b["dW"].sum(axis=0)).max() < 1e-14
+    assert abs((b["dH"] * H).sum() - (b["dW"] * W).sum()) < 1e-13
+    # the smoothed loss is the plain loss mixed with the cross-entropy against the uniform distribution
+    p0 = O.forward_per_row(H, W, y, IGN, 0.0)
+    Z = H @ W.T
+    unif = p0["lse"] - Z.mean(axis=1)
+    pe = O.forward_per_row(H, W, y, IGN, eps)
+    ok = y != IGN
+    np.testing.assert_allclose(pe["loss_rows"][ok], ((1 - eps) * p0["loss_rows"] + eps * unif)[ok], rtol=1e-13)
+
+
+@pytest.mark.parametrize("eps", [0.0, 0.2])
+def test_per_row_finite_differences(eps):
+    N, d, V = 5, 4, 7
+    H, W, y = rand_case(23, N, d, V, n_ignored=1, w_std=1.0)
+    gr = np.array([0.3, -1.2, 2.0, 0.9, 1.1])
+    b = O.backward_per_row(H, W, y, gr, IGN, eps)
+    h = 1e-6
+
+    def L(Hx, Wx):
+        return float(gr @ O.forward_per_row(Hx, Wx, y, IGN, eps)["loss_rows"])
+
+    for A, dA, which in ((H, b["dH"], 0), (W, b["dW"], 1)):
+        fd = np.zeros_like(A)
+        for idx in np.ndindex(*A.shape):
+            Ap, Am = A.copy(), A.copy()
+            Ap[idx] += h
+            Am[idx] -= h
+            fd[idx] = ((L(Ap, W) - L(Am, W)) if which == 0 else (L(H, Ap) - L(H, Am))) / (2 * h)
+        np.testing.assert_allclose(dA, fd, rtol=0, atol=5e-8)
+
+
+@pytest.mark.parametrize("eps", [0.0, 0.1])
+def test_per_row_against_torch_label_smoothing(eps):
+    torch = pytest.importorskip("torch")
+    H, W, y = rand_case(24, 29, 12, 41, n_ignored=4, w_std=1.0)
+    gr = np.random.default_rng(3).standard_normal(len(y))
+    Ht = torch.tensor(H, requires_grad=True)
+    Wt = torch.tensor(W, requires_grad=True)
+    rows = torch.nn.functional.cross_entropy(Ht @ Wt.T, torch.tensor(y), ignore_index=IGN, reduction="none",
+                                             label_smoothing=eps)
+    (rows * torch.tensor(gr)).sum().backward()
+    f = O.forward_per_row(H, W, y, IGN, eps)
+    b = O.backward_per_row(H, W, y, gr, IGN, eps)
+    np.testing.assert_allclose(f["loss_rows"], rows.detach().numpy(), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(b["dH"], Ht.grad.numpy(), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(b["dW"], Wt.grad.numpy(), rtol=0, atol=1e-13)
