@@ -143,6 +143,31 @@ flce_status flce_scale(const void* dH_partial, const void* dW_partial,
                        const void* workspace, void* dH_out, void* dW_out, void* hip_stream);
 
 /*
+ * Per-row variant (no reduction): one loss per row out of the forward, one upstream gradient per row
+ * into the backward (Alg. 2's Gamma given per position), optionally with label smoothing (the loss
+ * variant the Discussion names; reading taken: target distribution (1 - eps) onehot + eps / V, so
+ *   loss_i = (1 - eps) (lse_i - Z_{i,y_i}) + eps (lse_i - mean_v Z_iv),   dloss_i/dZ_iv = P_iv - q_v).
+ *   label_smoothing : eps in [0, 1); 0 gives the plain loss.
+ *   loss_rows_out   : device, N floats; 0 for rows that do not count.   lse_out as in flce_forward.
+ *   grad_rows       : device, N floats, d(total)/d(loss_i); ignored for rows that do not count.
+ *   dH_out = sum_v G_iv W_v, dW_out = sum_i G_iv H_i with G_iv = grad_rows[i] * (P_iv - q_v), G rounded to
+ *   `dt` after the scaling (the gradient differs per row, so it cannot wait for the output flush).
+ * mean_v Z_iv is computed as H_i . (sum_v W_v) / V (one pass over W, fixed summation order).
+ * Workspaces as for flce_forward / flce_backward; the header reports n_valid and the range flag.
+ */
+flce_status flce_forward_rows(const void* H, const void* W, const int64_t* targets,
+                              int64_t N, int64_t d, int64_t V, int64_t ignore_index,
+                              float label_smoothing, flce_dtype dt,
+                              float* loss_rows_out, float* lse_out,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+flce_status flce_backward_rows(const void* H, const void* W, const int64_t* targets, const float* lse,
+                               const float* grad_rows,
+                               int64_t N, int64_t d, int64_t V, int64_t ignore_index,
+                               float label_smoothing, flce_dtype dt,
+                               void* dH_out, void* dW_out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Vocabulary-sliced calls (Section "Model Parallelism", tensor parallelism: the outer loop restricted to
  * the local weight slice, partial results aggregated afterwards).  A slice is the V_slice vocabulary
  * rows [v_begin, v_begin + V_slice) of V_total, given as W_slice[V_slice][d]; targets stay global ids.

@@ -19,7 +19,7 @@ FLCE_DTYPE_BF16, FLCE_DTYPE_F32 = 0, 1
 FLCE_REDUCE_MEAN, FLCE_REDUCE_SUM = 0, 1
 
 EXPORTS = ("flce_version", "flce_status_string", "flce_workspace_bytes", "flce_forward", "flce_backward",
-           "flce_forward_with_grads", "flce_scale", "flce_forward_partial", "flce_merge_workspace_bytes",
+           "flce_forward_with_grads", "flce_scale", "flce_forward_rows", "flce_backward_rows", "flce_forward_partial", "flce_merge_workspace_bytes",
            "flce_merge_partials", "flce_backward_partial", "flce_last_device_status", "flce_profile_enable",
            "flce_profile_collect")
 PROF_CLASSES = ("fwd_tiles", "fwd_epilogue", "bwd_prep", "recompute", "contract_dW", "contract_dH", "scale")
@@ -55,6 +55,14 @@ def lib():
         L.flce_scale.restype = c.c_int
         L.flce_scale.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_int,
                                  c.c_float, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.flce_forward_rows.restype = c.c_int
+        L.flce_forward_rows.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_int64,
+                                        c.c_float, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t,
+                                        c.c_void_p]
+        L.flce_backward_rows.restype = c.c_int
+        L.flce_backward_rows.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64,
+                                         c.c_int64, c.c_int64, c.c_int64, c.c_float, c.c_int, c.c_void_p, c.c_void_p,
+                                         c.c_void_p, c.c_size_t, c.c_void_p]
         L.flce_forward_partial.restype = c.c_int
         L.flce_forward_partial.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
                                            c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_void_p, c.c_void_p,
@@ -130,6 +138,20 @@ def flce_forward_with_grads(H, W, targets, N, d, V, ignore_index, reduction, dt,
 def flce_scale(dH_partial, dW_partial, N, d, V, reduction, dt, grad_loss, workspace, dH_out, dW_out, hip_stream=None):
     return lib().flce_scale(_ptr(dH_partial), _ptr(dW_partial), N, d, V, reduction, dt, float(grad_loss),
                             _ptr(workspace), _ptr(dH_out), _ptr(dW_out), _stream(hip_stream))
+
+
+def flce_forward_rows(H, W, targets, N, d, V, ignore_index, label_smoothing, dt, loss_rows_out, lse_out, workspace,
+                      workspace_bytes, hip_stream=None):
+    return lib().flce_forward_rows(_ptr(H), _ptr(W), _ptr(targets), N, d, V, ignore_index, float(label_smoothing), dt,
+                                   _ptr(loss_rows_out), _ptr(lse_out), _ptr(workspace), workspace_bytes,
+                                   _stream(hip_stream))
+
+
+def flce_backward_rows(H, W, targets, lse, grad_rows, N, d, V, ignore_index, label_smoothing, dt, dH_out, dW_out,
+                       workspace, workspace_bytes, hip_stream=None):
+    return lib().flce_backward_rows(_ptr(H), _ptr(W), _ptr(targets), _ptr(lse), _ptr(grad_rows), N, d, V,
+                                    ignore_index, float(label_smoothing), dt, _ptr(dH_out), _ptr(dW_out),
+                                    _ptr(workspace), workspace_bytes, _stream(hip_stream))
 
 
 def flce_forward_partial(H, W_slice, targets, N, d, V_slice, v_begin, V_total, ignore_index, dt, m_out, a_out, zt_out,

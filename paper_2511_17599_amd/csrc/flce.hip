@@ -37,14 +37,14 @@ struct Plan {
   int64_t npad;
   // forward
   int n_win;
-  int64_t off_part, off_blk_loss, off_blk_cnt, off_blk_oor, off_fHT, fwd_bytes;
+  int64_t off_part, off_blk_loss, off_blk_cnt, off_blk_oor, off_wpart, off_wsum, off_zbar, off_fHT, fwd_bytes;
   // backward
   int n_vch, n_nch;        // chunks along vocabulary / tokens
   int vc_tiles, nc_tiles;  // largest chunk, in tiles
   bool fast;               // tuned bf16 loop: W, Hc and G read in place by the contractions
   bool hkr;                // forward / recompute read a transposed copy of H (needs its window within a descriptor's reach)
   int split_dh, split_dw;  // K slices of the dH / dW contraction launches (1 = unsplit)
-  int64_t off_Hc, off_rowmap, off_tgt, off_lsec, off_HT, off_WT, off_G, off_GT, off_dHacc, off_dWacc, off_partial, bwd_bytes;
+  int64_t off_Hc, off_rowmap, off_tgt, off_lsec, off_gamc, off_HT, off_WT, off_G, off_GT, off_dHacc, off_dWacc, off_partial, bwd_bytes;
 };
 
 // The tuned bf16 loop needs K extents that are multiples of 32 elements and every tile's address
@@ -84,6 +84,10 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   p.off_blk_loss = o;   o = align_up(o + (int64_t)p.n_rb * 4, ALIGN);
   p.off_blk_cnt = o;    o = align_up(o + (int64_t)p.n_rb * 4, ALIGN);
   p.off_blk_oor = o;    o = align_up(o + (int64_t)p.n_rb * 4, ALIGN);
+  // label smoothing (per-row forward): column sums of W by 1024-row chunks, their sum, mean logit per row
+  p.off_wpart = o;      o = align_up(o + ceil_div(V, 1024) * d * 4, ALIGN);
+  p.off_wsum = o;       o = align_up(o + d * 4, ALIGN);
+  p.off_zbar = o;       o = align_up(o + N * 4, ALIGN);
   p.off_fHT = o;        // sized below, once the loop flavour is known
   const int64_t fwd_fixed = o;
 
@@ -103,6 +107,7 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   p.off_rowmap = o; o = align_up(o + p.npad * 4, ALIGN);
   p.off_tgt = o;    o = align_up(o + p.npad * 4, ALIGN);
   p.off_lsec = o;   o = align_up(o + p.npad * 4, ALIGN);
+  p.off_gamc = o;   o = align_up(o + p.npad * 4, ALIGN);
   p.off_G = o;      o = align_up(o + nc_pad * vc_pad * p.esize, ALIGN);
   // K-contiguous copies, only for main loops that cannot read an operand across memory rows
   p.off_HT = o;     if (!p.fast || p.hkr) o = align_up(o + d * p.npad * p.esize, ALIGN);
@@ -185,9 +190,11 @@ hipError_t prepare_kernels() {
   hipError_t e;
   if ((e = allow_big_lds(fwd_tiles_kernel<T, L, false>, L::LDS)) != hipSuccess) return e;
   if ((e = allow_big_lds(recompute_kernel<T, L, false>, L::LDS)) != hipSuccess) return e;
+  if ((e = allow_big_lds(recompute_kernel<T, L, false, true>, L::LDS)) != hipSuccess) return e;
   if constexpr (L::TRANSPOSING) {
     if ((e = allow_big_lds(fwd_tiles_kernel<T, L, true>, L::LDS)) != hipSuccess) return e;
     if ((e = allow_big_lds(recompute_kernel<T, L, true>, L::LDS)) != hipSuccess) return e;
+    if ((e = allow_big_lds(recompute_kernel<T, L, true, true>, L::LDS)) != hipSuccess) return e;
   }
   if constexpr (L::TRANSPOSING) {
     if ((e = allow_big_lds(contract_kernel<T, L, OPS_DH_TR>, L::LDS)) != hipSuccess) return e;
@@ -201,11 +208,15 @@ hipError_t prepare_kernels() {
 // W holds the p.V vocabulary rows [slice.v_begin, slice.v_begin + p.V) of slice.V_total.  With m_out set the
 // call stops after the window merge and hands out the slice's (m, a, z_target) per row.
 struct Slice { int64_t V_total, v_begin; };
+// Per-row variant: the forward writes one loss per row (label-smoothed by eps), the backward takes one
+// upstream gradient per row (device arrays of N floats).
+struct PerRow { float* loss_rows_out; const float* grad_rows; float eps; };
 
 template <typename T, typename U, typename L>
 flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t* y, int64_t ignore_index,
                       int mean, float* loss_out, float* lse_out, char* ws, hipStream_t st, Slice slice,
-                      float* m_out = nullptr, float* a_out = nullptr, float* zt_out = nullptr) {
+                      float* m_out = nullptr, float* a_out = nullptr, float* zt_out = nullptr,
+                      PerRow rows = PerRow{nullptr, nullptr, 0.f}) {
   if (prepare_kernels<T, L>() != hipSuccess) return FLCE_ERR_HIP;
   Header* hdr = reinterpret_cast<Header*>(ws);
   float* part = reinterpret_cast<float*>(ws + p.off_part);
@@ -241,9 +252,24 @@ flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t
       merge_rows_partial_kernel<<<p.n_rb, 256, 0, st>>>(part, p.n_win, p.npad, (int)p.N, m_out, a_out, zt_out);
     } else {
       const int64_t plane = (int64_t)p.n_win * p.npad;
+      const float* zbar = nullptr;
+      if (rows.loss_rows_out && rows.eps != 0.f) {
+        float* wpart = reinterpret_cast<float*>(ws + p.off_wpart);
+        float* wsum = reinterpret_cast<float*>(ws + p.off_wsum);
+        float* zb = reinterpret_cast<float*>(ws + p.off_zbar);
+        const int n_chunks = (int)ceil_div(p.V, 1024);
+        colsum_chunks_kernel<T><<<n_chunks, 256, 0, st>>>(static_cast<const T*>(W), (int)p.V, (int)p.d, wpart);
+        colsum_finish_kernel<<<(unsigned)ceil_div(p.d, 256), 256, 0, st>>>(wpart, n_chunks, (int)p.d, wsum);
+        mean_logit_kernel<T><<<(unsigned)p.N, 256, 0, st>>>(static_cast<const T*>(H), wsum, (int)p.d,
+                                                            1.0f / (float)p.V, zb);
+        zbar = zb;
+      }
       merge_rows_kernel<<<p.n_rb, 256, 0, st>>>(part, part + plane, part + 2 * plane, p.n_win, p.npad, y, (int)p.N,
-                                                slice.V_total, ignore_index, lse_out, blk_loss, blk_cnt, blk_oor);
-      finalize_loss_kernel<<<1, 256, 0, st>>>(blk_loss, blk_cnt, blk_oor, p.n_rb, mean, hdr, loss_out);
+                                                slice.V_total, ignore_index, lse_out, blk_loss, blk_cnt, blk_oor,
+                                                rows.loss_rows_out, zbar, rows.eps);
+      // the per-row call has no scalar loss to hand out: the sum goes to a spare word of the header block
+      float* scalar = loss_out ? loss_out : reinterpret_cast<float*>(ws + 64);
+      finalize_loss_kernel<<<1, 256, 0, st>>>(blk_loss, blk_cnt, blk_oor, p.n_rb, mean, hdr, scalar);
     }
   }
   return hipGetLastError() == hipSuccess ? FLCE_OK : FLCE_ERR_HIP;
@@ -252,7 +278,7 @@ flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t
 template <typename T, typename U, typename L>
 flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_t* y, const float* lse,
                        int64_t ignore_index, int mean, float grad_loss, void* dH, void* dW, char* ws,
-                       hipStream_t st, Slice slice) {
+                       hipStream_t st, Slice slice, PerRow rows = PerRow{nullptr, nullptr, 0.f}) {
   if (prepare_kernels<T, L>() != hipSuccess) return FLCE_ERR_HIP;
   const int N = (int)p.N, d = (int)p.d, V = (int)p.V;
   Header* hdr = reinterpret_cast<Header*>(ws);
@@ -260,6 +286,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
   int* rowmap = reinterpret_cast<int*>(ws + p.off_rowmap);
   int* tgt_c = reinterpret_cast<int*>(ws + p.off_tgt);
   float* lse_c = reinterpret_cast<float*>(ws + p.off_lsec);
+  float* gam_c = reinterpret_cast<float*>(ws + p.off_gamc);
   T* HT = reinterpret_cast<T*>(ws + p.off_HT);
   T* WT = reinterpret_cast<T*>(ws + p.off_WT);
   T* G = reinterpret_cast<T*>(ws + p.off_G);
@@ -276,7 +303,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     compact_targets_kernel<<<1, 1024, 0, st>>>(y, N, V, slice.V_total, slice.v_begin, ignore_index, npad, rowmap,
                                                tgt_c, hdr);
     gather_rows_kernel<<<npad, 256, 0, st>>>(static_cast<const char*>(H), row_bytes, rowmap, lse,
-                                             reinterpret_cast<char*>(Hc), lse_c);
+                                             reinterpret_cast<char*>(Hc), lse_c, rows.grad_rows, gam_c);
     zero_uncounted_rows_kernel<<<N, 256, 0, st>>>(y, slice.V_total, ignore_index, static_cast<char*>(dH), row_bytes);
     if (!L::TRANSPOSING || p.hkr) {
       // Hc^T [d][npad]: the dW contraction's K-contiguous operand (generic loop), or the recompute's
@@ -306,7 +333,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     chunk_vt(vc, vt0, n_vt);
     chunk_nt(nc, nt0, n_nt);
     return RecomputeArgs<T>{Hc, HT, static_cast<const T*>(W), tgt_c, lse_c, hdr, npad, d, V, nt0, n_nt, vt0, n_vt,
-                            Gb, vc_pad, GT, nc_pad};
+                            Gb, vc_pad, GT, nc_pad, gam_c, 1.f - rows.eps, rows.eps / (float)slice.V_total};
   };
   // dW[vocab chunk] += G^T . Hc[row chunk]   (contraction over the compact rows of the chunk)
   auto dw_args = [&](int vc, int nc, const T* Gb) {
@@ -359,11 +386,15 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
       {
         const RecomputeArgs<T> rc = recompute_args(vc, nc, G);
         ProfScope ps(FLCE_PROF_RECOMPUTE, st);
+        const int grid = rc.n_nt * rc.n_vt;
         if (hkr) {
-          if constexpr (L::TRANSPOSING)
-            recompute_kernel<T, L, true><<<rc.n_nt * rc.n_vt, L::THREADS, L::LDS, st>>>(rc);
+          if constexpr (L::TRANSPOSING) {
+            if (rows.grad_rows) recompute_kernel<T, L, true, true><<<grid, L::THREADS, L::LDS, st>>>(rc);
+            else recompute_kernel<T, L, true><<<grid, L::THREADS, L::LDS, st>>>(rc);
+          }
         } else {
-          recompute_kernel<T, L, false><<<rc.n_nt * rc.n_vt, L::THREADS, L::LDS, st>>>(rc);
+          if (rows.grad_rows) recompute_kernel<T, L, false, true><<<grid, L::THREADS, L::LDS, st>>>(rc);
+          else recompute_kernel<T, L, false><<<grid, L::THREADS, L::LDS, st>>>(rc);
         }
       }
       {
@@ -420,10 +451,13 @@ size_t flce_workspace_bytes(int64_t N, int64_t d, int64_t V, flce_dtype dt, int 
 static flce_status forward_impl(const void* H, const void* W, const int64_t* targets, int64_t N, int64_t d,
                                 int64_t V, int64_t ignore_index, flce_reduction reduction, flce_dtype dt,
                                 float* loss_out, float* lse_out, void* workspace, size_t workspace_bytes,
-                                void* hip_stream, flce::Slice slice, float* m_out, float* a_out, float* zt_out) {
+                                void* hip_stream, flce::Slice slice, float* m_out, float* a_out, float* zt_out,
+                                flce::PerRow rows = flce::PerRow{nullptr, nullptr, 0.f}) {
   const bool partial = m_out || a_out || zt_out;
   if (!H || !W || !targets) return FLCE_ERR_BAD_ARG;
-  if (partial ? (!m_out || !a_out || !zt_out) : (!loss_out || !lse_out)) return FLCE_ERR_BAD_ARG;
+  if (partial ? (!m_out || !a_out || !zt_out) : ((!loss_out && !rows.loss_rows_out) || !lse_out))
+    return FLCE_ERR_BAD_ARG;
+  if (!(rows.eps >= 0.f && rows.eps < 1.f)) return FLCE_ERR_BAD_ARG;
   if (reduction != FLCE_REDUCE_MEAN && reduction != FLCE_REDUCE_SUM) return FLCE_ERR_BAD_ARG;
   if (dt != FLCE_DTYPE_BF16 && dt != FLCE_DTYPE_F32) return FLCE_ERR_BAD_ARG;
   flce::Plan p;
@@ -438,19 +472,23 @@ static flce_status forward_impl(const void* H, const void* W, const int64_t* tar
   if (dt == FLCE_DTYPE_BF16) {
     if (p.fast)
       return flce::forward_t<flce::bf16_t, uint16_t, flce::FastLoop>(p, H, W, targets, ignore_index, mean, loss_out,
-                                                                     lse_out, ws, st, slice, m_out, a_out, zt_out);
+                                                                     lse_out, ws, st, slice, m_out, a_out, zt_out,
+                                                                     rows);
     return flce::forward_t<flce::bf16_t, uint16_t, flce::GenericLoop<flce::bf16_t>>(
-        p, H, W, targets, ignore_index, mean, loss_out, lse_out, ws, st, slice, m_out, a_out, zt_out);
+        p, H, W, targets, ignore_index, mean, loss_out, lse_out, ws, st, slice, m_out, a_out, zt_out, rows);
   }
   return flce::forward_t<float, uint32_t, flce::GenericLoop<float>>(p, H, W, targets, ignore_index, mean, loss_out,
-                                                                    lse_out, ws, st, slice, m_out, a_out, zt_out);
+                                                                    lse_out, ws, st, slice, m_out, a_out, zt_out,
+                                                                    rows);
 }
 
 static flce_status backward_impl(const void* H, const void* W, const int64_t* targets, const float* lse, int64_t N,
                                  int64_t d, int64_t V, int64_t ignore_index, flce_reduction reduction, flce_dtype dt,
                                  float grad_loss, void* dH_out, void* dW_out, void* workspace, size_t workspace_bytes,
-                                 void* hip_stream, flce::Slice slice) {
+                                 void* hip_stream, flce::Slice slice,
+                                 flce::PerRow rows = flce::PerRow{nullptr, nullptr, 0.f}) {
   if (!H || !W || !targets || !lse || !dH_out || !dW_out) return FLCE_ERR_BAD_ARG;
+  if (!(rows.eps >= 0.f && rows.eps < 1.f)) return FLCE_ERR_BAD_ARG;
   if (reduction != FLCE_REDUCE_MEAN && reduction != FLCE_REDUCE_SUM) return FLCE_ERR_BAD_ARG;
   if (dt != FLCE_DTYPE_BF16 && dt != FLCE_DTYPE_F32) return FLCE_ERR_BAD_ARG;
   flce::Plan p;
@@ -466,12 +504,13 @@ static flce_status backward_impl(const void* H, const void* W, const int64_t* ta
   if (dt == FLCE_DTYPE_BF16) {
     if (p.fast)
       return flce::backward_t<flce::bf16_t, uint16_t, flce::FastLoop>(p, H, W, targets, lse, ignore_index, mean,
-                                                                      grad_loss, dH_out, dW_out, ws, st, slice);
+                                                                      grad_loss, dH_out, dW_out, ws, st, slice,
+                                                                      rows);
     return flce::backward_t<flce::bf16_t, uint16_t, flce::GenericLoop<flce::bf16_t>>(
-        p, H, W, targets, lse, ignore_index, mean, grad_loss, dH_out, dW_out, ws, st, slice);
+        p, H, W, targets, lse, ignore_index, mean, grad_loss, dH_out, dW_out, ws, st, slice, rows);
   }
   return flce::backward_t<float, uint32_t, flce::GenericLoop<float>>(p, H, W, targets, lse, ignore_index, mean,
-                                                                     grad_loss, dH_out, dW_out, ws, st, slice);
+                                                                     grad_loss, dH_out, dW_out, ws, st, slice, rows);
 }
 
 flce_status flce_forward(const void* H, const void* W, const int64_t* targets, int64_t N, int64_t d, int64_t V,
@@ -487,6 +526,25 @@ flce_status flce_backward(const void* H, const void* W, const int64_t* targets, 
                           void* hip_stream) {
   return backward_impl(H, W, targets, lse, N, d, V, ignore_index, reduction, dt, grad_loss, dH_out, dW_out,
                        workspace, workspace_bytes, hip_stream, flce::Slice{V, 0});
+}
+
+flce_status flce_forward_rows(const void* H, const void* W, const int64_t* targets, int64_t N, int64_t d, int64_t V,
+                              int64_t ignore_index, float label_smoothing, flce_dtype dt, float* loss_rows_out,
+                              float* lse_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!loss_rows_out) return FLCE_ERR_BAD_ARG;
+  return forward_impl(H, W, targets, N, d, V, ignore_index, FLCE_REDUCE_SUM, dt, nullptr, lse_out, workspace,
+                      workspace_bytes, hip_stream, flce::Slice{V, 0}, nullptr, nullptr, nullptr,
+                      flce::PerRow{loss_rows_out, nullptr, label_smoothing});
+}
+
+flce_status flce_backward_rows(const void* H, const void* W, const int64_t* targets, const float* lse,
+                               const float* grad_rows, int64_t N, int64_t d, int64_t V, int64_t ignore_index,
+                               float label_smoothing, flce_dtype dt, void* dH_out, void* dW_out, void* workspace,
+                               size_t workspace_bytes, void* hip_stream) {
+  if (!grad_rows) return FLCE_ERR_BAD_ARG;
+  return backward_impl(H, W, targets, lse, N, d, V, ignore_index, FLCE_REDUCE_SUM, dt, 1.0f, dH_out, dW_out,
+                       workspace, workspace_bytes, hip_stream, flce::Slice{V, 0},
+                       flce::PerRow{nullptr, grad_rows, label_smoothing});
 }
 
 flce_status flce_forward_partial(const void* H, const void* W_slice, const int64_t* targets, int64_t N, int64_t d,
@@ -524,7 +582,8 @@ flce_status flce_merge_partials(const float* m_parts, const float* a_parts, cons
   int* blk_oor = reinterpret_cast<int*>(ws + flce::ALIGN + 2 * blk);
   flce::ProfScope ps(FLCE_PROF_FWD_EPILOGUE, st);
   flce::merge_rows_kernel<<<n_rb, 256, 0, st>>>(m_parts, a_parts, zt_parts, n_parts, N, targets, (int)N, V_total,
-                                                ignore_index, lse_out, blk_loss, blk_cnt, blk_oor);
+                                                ignore_index, lse_out, blk_loss, blk_cnt, blk_oor, nullptr, nullptr,
+                                                0.f);
   flce::finalize_loss_kernel<<<1, 256, 0, st>>>(blk_loss, blk_cnt, blk_oor, n_rb, reduction == FLCE_REDUCE_MEAN, hdr,
                                                 loss_out);
   return hipGetLastError() == hipSuccess ? FLCE_OK : FLCE_ERR_HIP;

@@ -86,6 +86,34 @@ struct Header {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Four consecutive elements of the storage type <-> four floats.
+template <typename T> struct Pack4;
+template <> struct Pack4<float> {
+  static __device__ __forceinline__ void store(float* p, float a, float b, float c, float d) {
+    *reinterpret_cast<f32x4*>(p) = f32x4{a, b, c, d};
+  }
+  static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
+    const f32x4 x = *reinterpret_cast<const f32x4*>(p);
+    v[0] = x[0]; v[1] = x[1]; v[2] = x[2]; v[3] = x[3];
+  }
+  static __device__ __forceinline__ float one(float v) { return v; }
+};
+template <> struct Pack4<bf16_t> {
+  static __device__ __forceinline__ void store(bf16_t* p, float a, float b, float c, float d) {
+    uint2 v;
+    v.x = (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
+    v.y = (uint32_t)f32_to_bf16_bits(c) | ((uint32_t)f32_to_bf16_bits(d) << 16);
+    *reinterpret_cast<uint2*>(p) = v;
+  }
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[4]) {
+    const uint2 x = *reinterpret_cast<const uint2*>(p);
+    v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xFFFF0000u);
+    v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xFFFF0000u);
+  }
+  static __device__ __forceinline__ bf16_t one(float v) { return bf16_t{f32_to_bf16_bits(v)}; }
+};
+
+
 // Whether a row counts towards the loss: its target is not the ignore index and lies in
 // [0, V_total); a target outside that range that is not the ignore index is reported through `oor`.
 __device__ __forceinline__ bool target_counts(int64_t y, int64_t ignore_index, int64_t V_total, bool& oor) {
@@ -261,11 +289,13 @@ __device__ __forceinline__ void merge_parts_of_row(const float* __restrict__ pm,
   }
 }
 
-// lse = M + ln A, loss_i = lse - z_target for counted rows; per-block sums in a fixed tree.
+// lse = M + ln A, loss_i = lse - z_target for counted rows (optionally label-smoothed and written out
+// per row); per-block sums in a fixed tree.
 __global__ __launch_bounds__(256) void merge_rows_kernel(
     const float* __restrict__ pm, const float* __restrict__ pa, const float* __restrict__ pz, int n_parts,
     int64_t stride, const int64_t* __restrict__ y, int N, int64_t V_total, int64_t ignore_index,
-    float* __restrict__ lse_out, float* __restrict__ blk_loss, int* __restrict__ blk_cnt, int* __restrict__ blk_oor) {
+    float* __restrict__ lse_out, float* __restrict__ blk_loss, int* __restrict__ blk_cnt, int* __restrict__ blk_oor,
+    float* __restrict__ loss_rows_out, const float* __restrict__ zbar, float eps) {
   __shared__ float sh[256];
   const int n = blockIdx.x * 256 + threadIdx.x;
   float loss = 0.f, cnt = 0.f, bad = 0.f;
@@ -275,8 +305,15 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(
     const float lse = M + logf(A);
     lse_out[n] = lse;
     bool oor;
-    if (target_counts(y[n], ignore_index, V_total, oor)) { loss = lse - z; cnt = 1.f; }
+    if (target_counts(y[n], ignore_index, V_total, oor)) {
+      loss = lse - z;
+      // label smoothing: the target distribution keeps 1 - eps on y_i and spreads eps evenly, so
+      // the row's loss mixes in eps * (lse - mean_v Z_iv)
+      if (zbar) loss = (1.f - eps) * loss + eps * (lse - zbar[n]);
+      cnt = 1.f;
+    }
     if (oor) bad = 1.f;
+    if (loss_rows_out) loss_rows_out[n] = loss;
   }
   const float bl = block_sum_256(loss, sh);
   const float bc = block_sum_256(cnt, sh);     // <= 256: exact in fp32
@@ -286,6 +323,49 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(
     blk_cnt[blockIdx.x] = (int)bc;
     blk_oor[blockIdx.x] = bb > 0.f ? 1 : 0;
   }
+}
+
+// mean_v Z_iv = H_i . (sum_v W_v) / V, for label smoothing: the column sums of W in two fixed-order
+// steps (1024-row chunks, then the chunks in order), then one dot product per row.
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_chunks_kernel(const T* __restrict__ W, int V, int d,
+                                                            float* __restrict__ wpart) {
+  const int r0 = blockIdx.x * 1024, r1 = min(V, r0 + 1024);
+  for (int m = threadIdx.x * 4; m < d; m += 1024) {
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int r = r0; r < r1; ++r) {
+      float v[4];
+      Pack4<T>::load(W + (int64_t)r * d + m, v);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[e] += v[e];
+    }
+    *reinterpret_cast<f32x4*>(wpart + (int64_t)blockIdx.x * d + m) = f32x4{acc[0], acc[1], acc[2], acc[3]};
+  }
+}
+
+__global__ __launch_bounds__(256) void colsum_finish_kernel(const float* __restrict__ wpart, int n_chunks, int d,
+                                                            float* __restrict__ wsum) {
+  const int m = blockIdx.x * 256 + threadIdx.x;
+  if (m >= d) return;
+  float acc = 0.f;
+  for (int c = 0; c < n_chunks; ++c) acc += wpart[(int64_t)c * d + m];
+  wsum[m] = acc;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void mean_logit_kernel(const T* __restrict__ H, const float* __restrict__ wsum,
+                                                         int d, float inv_V, float* __restrict__ zbar) {
+  __shared__ float sh[256];
+  const int n = blockIdx.x;
+  float acc = 0.f;
+  for (int m = threadIdx.x * 4; m < d; m += 1024) {
+    float v[4];
+    Pack4<T>::load(H + (int64_t)n * d + m, v);
+    const f32x4 w = *reinterpret_cast<const f32x4*>(wsum + m);
+    acc += v[0] * w[0] + v[1] * w[1] + v[2] * w[2] + v[3] * w[3];
+  }
+  const float tot = block_sum_256(acc, sh);
+  if (threadIdx.x == 0) zbar[n] = tot * inv_V;
 }
 
 // The window merge of a call that covers one vocabulary slice: the slice's (m, a, z_target) per row,
@@ -384,12 +464,15 @@ __global__ __launch_bounds__(1024) void compact_targets_kernel(const int64_t* __
   }
 }
 
-// Hc[c][:] = H[rowmap[c]][:], lse_c[c] = lse[rowmap[c]]; zero rows where rowmap[c] < 0.
+// Hc[c][:] = H[rowmap[c]][:], lse_c[c] = lse[rowmap[c]] (and the row's upstream gradient, if given); zero rows
+// where rowmap[c] < 0.
 // One block per compact row; rows are copied as 16-byte vectors (row_bytes % 16 == 0).
 __global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict__ H, int64_t row_bytes,
                                                           const int* __restrict__ rowmap,
                                                           const float* __restrict__ lse, char* __restrict__ Hc,
-                                                          float* __restrict__ lse_c) {
+                                                          float* __restrict__ lse_c,
+                                                          const float* __restrict__ grad_rows,
+                                                          float* __restrict__ gam_c) {
   const int c = blockIdx.x;
   const int n = rowmap[c];
   const u32x4 z = {0u, 0u, 0u, 0u};
@@ -397,7 +480,10 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict
   u32x4* dst = reinterpret_cast<u32x4*>(Hc + (int64_t)c * row_bytes);
   const int nvec = (int)(row_bytes / 16);
   for (int i = threadIdx.x; i < nvec; i += 256) dst[i] = (n >= 0) ? src[i] : z;
-  if (threadIdx.x == 0) lse_c[c] = (n >= 0) ? lse[n] : 0.f;
+  if (threadIdx.x == 0) {
+    lse_c[c] = (n >= 0) ? lse[n] : 0.f;
+    if (grad_rows) gam_c[c] = (n >= 0) ? grad_rows[n] : 0.f;
+  }
 }
 
 // dH rows of tokens that do not count are exactly +0.  One block per row.
@@ -437,32 +523,6 @@ __global__ __launch_bounds__(256) void transpose_pad_kernel(const U* __restrict_
   }
 }
 
-template <typename T> struct Pack4;
-template <> struct Pack4<float> {
-  static __device__ __forceinline__ void store(float* p, float a, float b, float c, float d) {
-    *reinterpret_cast<f32x4*>(p) = f32x4{a, b, c, d};
-  }
-  static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
-    const f32x4 x = *reinterpret_cast<const f32x4*>(p);
-    v[0] = x[0]; v[1] = x[1]; v[2] = x[2]; v[3] = x[3];
-  }
-  static __device__ __forceinline__ float one(float v) { return v; }
-};
-template <> struct Pack4<bf16_t> {
-  static __device__ __forceinline__ void store(bf16_t* p, float a, float b, float c, float d) {
-    uint2 v;
-    v.x = (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
-    v.y = (uint32_t)f32_to_bf16_bits(c) | ((uint32_t)f32_to_bf16_bits(d) << 16);
-    *reinterpret_cast<uint2*>(p) = v;
-  }
-  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[4]) {
-    const uint2 x = *reinterpret_cast<const uint2*>(p);
-    v[0] = __uint_as_float(x.x << 16); v[1] = __uint_as_float(x.x & 0xFFFF0000u);
-    v[2] = __uint_as_float(x.y << 16); v[3] = __uint_as_float(x.y & 0xFFFF0000u);
-  }
-  static __device__ __forceinline__ bf16_t one(float v) { return bf16_t{f32_to_bf16_bits(v)}; }
-};
-
 // ------------------------------------------------------------------------------------
 // Backward, step 1 (on the compacted rows): logit tile recomputed exactly as in the
 // forward, then
@@ -480,10 +540,15 @@ struct RecomputeArgs {
   const T* Hc; const T* HcT; const T* W; const int* tgt_c; const float* lse_c; const Header* hdr;
   int npad, d, V, nt0, n_nt, vt0, n_vt;
   T* G; int64_t ldG; T* GT; int64_t ldGT;
+  // per-row variant only: upstream gradient of each compact row, label-smoothing constants
+  const float* gam_c; float onehot_weight; float uniform_part;   // 1 - eps, eps / V
 };
 
 // One tile of the recompute step; `bid` of `nblocks` tiles of this launch.
-template <typename T, typename L, bool HKR>
+// PER_ROW: g = Gamma_row * (p - (1 - eps) [v == y_row] - eps / V), the upstream gradient applied here because
+// it differs from row to row (Alg. 2 with a per-position Gamma); otherwise g = p - [v == y_row] and the
+// scalar Gamma is applied when the contractions write out.
+template <typename T, typename L, bool HKR, bool PER_ROW = false>
 __device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bid, int nblocks, char* lds) {
   const T* __restrict__ Hc = a.Hc; const T* __restrict__ HcT = a.HcT; const T* __restrict__ W = a.W;
   const int* __restrict__ tgt_c = a.tgt_c; const float* __restrict__ lse_c = a.lse_c;
@@ -512,6 +577,8 @@ __device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bi
     const int tgt = tgt_c[n];
     const bool counted = tgt >= 0;
     const float l = lse_c[n];
+    float gam = 1.f;
+    if constexpr (PER_ROW) gam = a.gam_c[n];
 #pragma unroll
     for (int i = 0; i < L::WM; ++i)
 #pragma unroll
@@ -521,7 +588,9 @@ __device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bi
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int v = v0 + mloc + e;
-          float pz = fast_exp2((acc[i][j][rq * 4 + e] - l) * LOG2E) - ((v == tgt) ? 1.f : 0.f);
+          float pz = fast_exp2((acc[i][j][rq * 4 + e] - l) * LOG2E);
+          if constexpr (PER_ROW) pz = gam * (pz - ((v == tgt) ? a.onehot_weight : 0.f) - a.uniform_part);
+          else pz -= (v == tgt) ? 1.f : 0.f;
           g[e] = (counted && v < V) ? pz : 0.f;
         }
         const int vl = q * TILE + mloc;
@@ -535,10 +604,10 @@ __device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bi
   }
 }
 
-template <typename T, typename L, bool HKR>
+template <typename T, typename L, bool HKR, bool PER_ROW = false>
 __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> a) {
   extern __shared__ __align__(16) char lds[];
-  recompute_tile<T, L, HKR>(a, blockIdx.x, gridDim.x, lds);
+  recompute_tile<T, L, HKR, PER_ROW>(a, blockIdx.x, gridDim.x, lds);
 }
 
 // ------------------------------------------------------------------------------------

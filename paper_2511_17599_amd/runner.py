@@ -69,6 +69,17 @@ class Session:
         return B.flce_scale(self.dH, self.dW, self.N, self.d, self.V, self.red, self.dt, self.grad_loss, self.ws,
                             self.dH, self.dW, self.stream())
 
+    def forward_rows(self, loss_rows, label_smoothing=0.0):
+        """One loss per row into `loss_rows` (device, N floats)."""
+        return B.flce_forward_rows(self.H, self.W, self.y, self.N, self.d, self.V, self.ignore_index, label_smoothing,
+                                   self.dt, loss_rows, self.lse, self.ws, self.fwd_bytes, self.stream())
+
+    def backward_rows(self, grad_rows, label_smoothing=0.0):
+        """Gradients of sum_i grad_rows[i] * loss_i (grad_rows: device, N floats)."""
+        return B.flce_backward_rows(self.H, self.W, self.y, self.lse, grad_rows, self.N, self.d, self.V,
+                                    self.ignore_index, label_smoothing, self.dt, self.dH, self.dW, self.ws,
+                                    self.bwd_bytes, self.stream())
+
     def device_status(self):
         return B.flce_last_device_status(self.ws, self.stream())
 

@@ -103,3 +103,15 @@ def test_bad_arguments_are_rejected_without_a_device():
     assert bp(Vt=100) == B.FLCE_ERR_BAD_SHAPE
     assert bp(dW=None) == B.FLCE_ERR_BAD_ARG
     assert bp(wsb=16) == B.FLCE_ERR_WORKSPACE
+    # per-row variant: label smoothing must lie in [0, 1); the per-row arrays must be there
+    fr = lambda **kw: B.flce_forward_rows(p, p, p, 256, 64, 512, -100, kw.get("eps", 0.1), B.FLCE_DTYPE_F32,
+                                          kw.get("rows", p), p, p, need_f)
+    assert fr(eps=1.0) == B.FLCE_ERR_BAD_ARG
+    assert fr(eps=-0.1) == B.FLCE_ERR_BAD_ARG
+    assert fr(eps=float("nan")) == B.FLCE_ERR_BAD_ARG
+    assert fr(rows=None) == B.FLCE_ERR_BAD_ARG
+    br = lambda **kw: B.flce_backward_rows(p, p, p, p, kw.get("g", p), 256, 64, 512, -100, kw.get("eps", 0.0),
+                                           B.FLCE_DTYPE_F32, p, p, p, kw.get("wsb", need_b))
+    assert br(g=None) == B.FLCE_ERR_BAD_ARG
+    assert br(eps=1.5) == B.FLCE_ERR_BAD_ARG
+    assert br(wsb=need_b - 1) == B.FLCE_ERR_WORKSPACE

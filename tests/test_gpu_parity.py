@@ -293,3 +293,38 @@ def test_vocabulary_slices_merge_to_the_whole(dtype, reduction):
     whole = run_workload(wl, x, grad_loss=0.5)
     assert np.abs(whole["lse"] - got["lse"]).max() <= 4e-6 * np.abs(f["lse"]).max()
     assert nerr(whole["dW"], got["dW"]) <= (1e-2 if dtype == "bf16" else 1e-5)
+
+
+@pytest.mark.parametrize("dtype,eps,generic", [("bf16", 0.0, 0), ("bf16", 0.1, 0), ("bf16", 0.1, 1), ("f32", 0.2, 0)])
+def test_per_row_losses_and_gradients(monkeypatch, dtype, eps, generic):
+    """No reduction: one loss per row out, one upstream gradient per row in, with and without label smoothing,
+    against the oracle's per-row functions (several chunks in the backward)."""
+    from paper_2511_17599_amd.runner import session_for, to_host_f64, to_device
+    monkeypatch.setenv("FLCE_GENERIC", str(generic))
+    monkeypatch.setenv("FLCE_VC_TILES", "3")
+    monkeypatch.setenv("FLCE_NC_TILES", "2")
+    wl = custom(f"rows_{dtype}_{eps}_{generic}", 900, 160, 1700, dtype, 95, ignore_frac=0.1)
+    x = I.make_inputs(wl)
+    x["y"][11] = 5000                                        # outside the vocabulary: dropped and flagged
+    print(f"[case] {wl.name} per-row, label smoothing {eps}", flush=True)
+    gr = (np.random.default_rng(9).standard_normal(wl.N) * 0.5 + 1.0).astype(np.float32)
+    s = session_for(wl, x)
+    loss_rows = torch.empty(wl.N, dtype=torch.float32, device=s.device)
+    assert s.forward_rows(loss_rows, eps) == B.FLCE_OK
+    st, nv = s.device_status()
+    assert s.backward_rows(to_device(gr, s.device), eps) == B.FLCE_OK
+    stb, nvb = s.device_status()
+    Hd, Wd = I.to_f64(x["H"]), I.to_f64(x["W"])
+    f = O.forward_per_row(Hd, Wd, x["y"], wl.ignore_index, eps)
+    b = O.backward_per_row(Hd, Wd, x["y"], gr.astype(np.float64), wl.ignore_index, eps)
+    tol = TOL[dtype]
+    assert st == stb == B.FLCE_ERR_TARGET_RANGE and nv == nvb == f["n_valid"]
+    lr = to_host_f64(loss_rows)
+    assert not lr[~f["valid"]].any()                         # rows that do not count: exactly 0
+    assert np.abs(lr - f["loss_rows"]).max() <= tol["loss"] * np.abs(f["loss_rows"]).max()
+    assert np.abs(to_host_f64(s.lse) - f["lse"]).max() <= tol["lse"] * np.abs(f["lse"]).max()
+    eH, eW = nerr(to_host_f64(s.dH), b["dH"]), nerr(to_host_f64(s.dW), b["dW"])
+    print(f"       dH {eH:.2e}  dW {eW:.2e}", flush=True)
+    assert eH <= tol["grad"] and eW <= tol["grad"]
+    raw = s.dH.view(torch.int16 if dtype == "bf16" else torch.int32).cpu().numpy()
+    assert not raw[~f["valid"]].any()
