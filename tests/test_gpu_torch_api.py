@@ -1,0 +1,66 @@
+"""The torch.autograd front end against the CPU fp64 oracle (it only marshals arguments: the numbers come from the
+same library calls the other GPU tests cover)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import flce_oracle as O                       # noqa: E402
+from paper_2511_17599_amd import inputs as I              # noqa: E402
+from paper_2511_17599_amd.runner import to_device         # noqa: E402
+
+
+@pytest.fixture(autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+
+
+def nerr(got, ref):
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300))
+
+
+def tensors(wl, x):
+    H = to_device(x["H"], "cuda:0").reshape(4, wl.N // 4, wl.d).requires_grad_(True)      # [batch, seq, d]
+    W = to_device(x["W"], "cuda:0").requires_grad_(True)
+    y = to_device(x["y"], "cuda:0").reshape(4, wl.N // 4)
+    return H, W, y
+
+
+@pytest.mark.parametrize("reduction,eps", [("mean", 0.0), ("sum", 0.0), ("mean", 0.1)])
+def test_scalar_losses(reduction, eps):
+    from paper_2511_17599_amd.torch_api import linear_cross_entropy
+    wl = I.Workload("api", 512, 96, 1000, "bf16", "uniform", ignore_frac=0.1, reduction=reduction, seed=301)
+    x = I.make_inputs(wl)
+    H, W, y = tensors(wl, x)
+    loss = linear_cross_entropy(H, W, y, reduction=reduction, label_smoothing=eps)
+    (loss * 1.5).backward()
+    Hd, Wd = I.to_f64(x["H"]), I.to_f64(x["W"])
+    f = O.forward_per_row(Hd, Wd, x["y"], wl.ignore_index, eps)
+    scale = 1.5 / f["n_valid"] if reduction == "mean" else 1.5
+    want = f["loss_rows"].sum() * scale / 1.5
+    b = O.backward_per_row(Hd, Wd, x["y"], np.full(wl.N, scale), wl.ignore_index, eps)
+    assert abs(loss.item() - want) <= 2e-3 * abs(want)
+    assert H.grad.shape == H.shape and W.grad.shape == W.shape
+    assert nerr(H.grad.float().cpu().numpy().reshape(wl.N, wl.d).astype(np.float64), b["dH"]) <= 2e-2
+    assert nerr(W.grad.float().cpu().numpy().astype(np.float64), b["dW"]) <= 2e-2
+
+
+def test_row_losses_with_their_own_weights():
+    from paper_2511_17599_amd.torch_api import linear_cross_entropy
+    wl = I.Workload("api_rows", 512, 64, 700, "f32", "uniform", ignore_frac=0.1, seed=302)
+    x = I.make_inputs(wl)
+    H, W, y = tensors(wl, x)
+    rows = linear_cross_entropy(H, W, y, reduction="none")
+    assert rows.shape == y.shape
+    wts = torch.linspace(0.5, 2.0, wl.N, device="cuda:0").reshape(y.shape)
+    (rows * wts).sum().backward()
+    Hd, Wd = I.to_f64(x["H"]), I.to_f64(x["W"])
+    f = O.forward_per_row(Hd, Wd, x["y"], wl.ignore_index, 0.0)
+    b = O.backward_per_row(Hd, Wd, x["y"], wts.reshape(-1).cpu().numpy().astype(np.float64), wl.ignore_index, 0.0)
+    got = rows.detach().cpu().numpy().reshape(-1).astype(np.float64)
+    assert np.abs(got - f["loss_rows"]).max() <= 1e-5 * np.abs(f["loss_rows"]).max()
+    assert nerr(H.grad.cpu().numpy().reshape(wl.N, wl.d).astype(np.float64), b["dH"]) <= 1e-4
+    assert nerr(W.grad.cpu().numpy().astype(np.float64), b["dW"]) <= 1e-4
