@@ -208,9 +208,10 @@ __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
         for (int r = 1; r < 16; ++r) bmax = fmaxf(bmax, z[r]);
         const float mn = fmaxf(m[j], bmax);
         const float ms = (mn == NEG_INF) ? 0.f : mn;     // nothing but padding so far: keep exp arguments finite
+        const float msl = -ms * LOG2E;                   // exp(z - ms) = 2^(z * log2e - ms * log2e): one fma per logit
         float sum = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sum += fast_exp2((z[r] - ms) * LOG2E);
+        for (int r = 0; r < 16; ++r) sum += fast_exp2(fmaf(z[r], LOG2E, msl));
         a[j] = a[j] * fast_exp2((m[j] - ms) * LOG2E) + sum;
         m[j] = mn;
 
@@ -577,6 +578,7 @@ __device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bi
     const int tgt = tgt_c[n];
     const bool counted = tgt >= 0;
     const float l = lse_c[n];
+    const float ll = -l * LOG2E;                      // exp(z - lse) = 2^(z * log2e - lse * log2e)
     float gam = 1.f;
     if constexpr (PER_ROW) gam = a.gam_c[n];
 #pragma unroll
@@ -588,7 +590,7 @@ __device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bi
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int v = v0 + mloc + e;
-          float pz = fast_exp2((acc[i][j][rq * 4 + e] - l) * LOG2E);
+          float pz = fast_exp2(fmaf(acc[i][j][rq * 4 + e], LOG2E, ll));
           if constexpr (PER_ROW) pz = gam * (pz - ((v == tgt) ? a.onehot_weight : 0.f) - a.uniform_part);
           else pz -= (v == tgt) ? 1.f : 0.f;
           g[e] = (counted && v < V) ? pz : 0.f;
