@@ -101,8 +101,8 @@ template <> struct Pack4<float> {
 template <> struct Pack4<bf16_t> {
   static __device__ __forceinline__ void store(bf16_t* p, float a, float b, float c, float d) {
     uint2 v;
-    v.x = (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16);
-    v.y = (uint32_t)f32_to_bf16_bits(c) | ((uint32_t)f32_to_bf16_bits(d) << 16);
+    v.x = f32x2_to_bf16x2_bits(a, b);
+    v.y = f32x2_to_bf16x2_bits(c, d);
     *reinterpret_cast<uint2*>(p) = v;
   }
   static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[4]) {

@@ -34,11 +34,16 @@ constexpr int LDS_BYTES = 2 * STAGE_BYTES;       // double buffered: 128 KiB
 
 struct bf16_t { uint16_t bits; };
 
+// fp32 -> bf16, round to nearest even: gfx950 converts in hardware (v_cvt_pk_bf16_f32), two values per
+// instruction.
+typedef __bf16 hw_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float hw_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2_bits(float lo, float hi) {
+  const hw_bf16x2 b = __builtin_convertvector(hw_f32x2{lo, hi}, hw_bf16x2);
+  return __builtin_bit_cast(uint32_t, b);
+}
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  // round to nearest even; NaN never occurs on this path
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+  return __builtin_bit_cast(uint16_t, (__bf16)f);
 }
 
 __device__ __forceinline__ int lds_off(int row, int chunk) {
