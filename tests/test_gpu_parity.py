@@ -82,6 +82,11 @@ def test_tiny_f32_workload():
     custom("bf16_small_everything", 5, 8, 3, "bf16", 14),
     custom("f32_single_row", 1, 8, 1, "f32", 15),
     custom("bf16_zipf_sum", 1030, 256, 2049, "bf16", 16, targets="zipf", reduction="sum"),
+    # the tuned bf16 loop (d a multiple of 32) at degenerate extents
+    custom("bf16_tuned_one_row_one_word", 1, 32, 1, "bf16", 17),
+    custom("bf16_tuned_few_rows", 3, 64, 300, "bf16", 18),
+    custom("bf16_tuned_two_words", 300, 64, 2, "bf16", 19, ignore_frac=0.3),
+    custom("bf16_tuned_257", 257, 32, 257, "bf16", 20, ignore_frac=0.5),
 ], ids=lambda w: w.name)
 def test_ragged_and_small_shapes(wl):
     check_against_oracle(wl, I.make_inputs(wl), grad_loss=1.0 if wl.reduction == "mean" else -0.75)
