@@ -115,3 +115,18 @@ def test_bad_arguments_are_rejected_without_a_device():
     assert br(g=None) == B.FLCE_ERR_BAD_ARG
     assert br(eps=1.5) == B.FLCE_ERR_BAD_ARG
     assert br(wsb=need_b - 1) == B.FLCE_ERR_WORKSPACE
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary header compiles as C99 on its own (no C++ or HIP types in the signatures)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_flce.c"
+    src.write_text('#include "flce.h"\nint main(void) { flce_status (*f)(int) = flce_profile_enable; return f == 0 ? FLCE_PROF_CLASSES : FLCE_OK; }\n')
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
