@@ -26,8 +26,8 @@ F32_MFMA_PEAK_TFLOPS = 157.3
 # same counters' reading for a plain 1 GiB copy (profiles/llama3_8b_pmc.txt); only for the default launch
 # configuration of the workload they were taken on, otherwise null.
 MEASURED_TRAFFIC = {
-    "llama3_8b": {"fwd_tiles": 14.087e9 + 0.568e9, "recompute": 3.525e9 + 0.477e9,
-                  "contract_dW": 3.404e9 + 0.327e9, "contract_dH": 3.657e9 + 0.115e9},
+    "llama3_8b": {"fwd_tiles": 14.365e9 + 0.568e9, "recompute": 3.447e9 + 0.477e9,
+                  "contract_dW": 3.398e9 + 0.330e9, "contract_dH": 3.631e9 + 0.115e9},
 }
 
 
