@@ -131,6 +131,9 @@ def main():
     ap.add_argument("--path", choices=["recompute", "partial_grads"], default="recompute",
                     help="recompute: forward (Alg. 1) + backward (Alg. 2), the benchmarked path; partial_grads: "
                          "forward with partial gradients (Alg. 3) + scaling (Alg. 4)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time its replays (launch-bound shapes); implies "
+                         "--no-profile")
     ap.add_argument("--sweep", choices=["paper_table2"], default=None,
                     help="instead of the benchmark line: latency and memory over the paper's evaluation grid")
     args = ap.parse_args()
@@ -174,11 +177,24 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run_step = step
+    if args.graph:
+        args.no_profile = True
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        run_step = graph.replay
+        run_step()
+        torch.cuda.synchronize()
     if not args.no_profile:
         B.flce_profile_enable(1)
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof_ms, prof_n = {}, {}
@@ -236,7 +252,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "d": wl.d, "V": wl.V, "reduction": wl.reduction,
-                   "targets": wl.targets, "ignore_frac": wl.ignore_frac, "seed": wl.seed, "path": args.path},
+                   "targets": wl.targets, "ignore_frac": wl.ignore_frac, "seed": wl.seed, "path": args.path, "launch": "graph replay" if args.graph else "eager"},
         "tflops_8NdV": tflops, "frac_of_mfma_peak": tflops / peak,
         "tflops_executed": flops_executed / (ms_per_step * 1e-3) / 1e12,
         "flops_note": "8NdV counts the ignored rows too; the backward skips them (their rows of G are zero), "
