@@ -41,6 +41,8 @@ struct Plan {
   // backward
   int n_vch, n_nch;        // chunks along vocabulary / tokens
   int vc_tiles, nc_tiles;  // largest chunk, in tiles
+  int64_t ld_v, ld_n;      // elements per row of the buffers whose rows run over a vocabulary / row chunk: the
+                           // chunk's extent plus 64, so that rows never lie a power of two apart
   bool fast;               // tuned bf16 loop: W, Hc and G read in place by the contractions
   bool hkr;                // forward / recompute read a transposed copy of H (needs its window within a descriptor's reach)
   int split_dh, split_dw;  // K slices of the dH / dW contraction launches (1 = unsplit)
@@ -48,16 +50,14 @@ struct Plan {
 };
 
 // The tuned bf16 loop needs K extents that are multiples of 32 elements and every tile's address
-// window within reach of a buffer descriptor: offsets are unsigned 32-bit, the bytes actually read
-// stay below 2^31, and the zero-filled overshoot of a last K stage (up to 32 rows) must not wrap
-// 2^32.  FLCE_GENERIC=1 forces the generic loop everywhere.
-bool window_ok(int64_t k_rows, int64_t ld_bytes) {
-  return k_rows * ld_bytes <= ((int64_t)1 << 31) && (k_rows + 32) * ld_bytes < ((int64_t)1 << 32);
-}
+// window within reach of a buffer descriptor: offsets and the record count are unsigned 32-bit, and
+// the zero-filled overshoot of a last K stage (up to 32 rows) must not wrap 2^32.
+// FLCE_GENERIC=1 forces the generic loop everywhere.
+bool window_ok(int64_t k_rows, int64_t ld_bytes) { return (k_rows + 32) * ld_bytes < ((int64_t)1 << 32); }
 bool fast_loop_ok(const Plan& p) {
   if (p.esize != 2 || env_int("FLCE_GENERIC", 0, 0, 1)) return false;
   const int64_t vc = (int64_t)p.vc_tiles * TILE, nc = (int64_t)p.nc_tiles * TILE;
-  const int64_t ld_hw = p.d * 2, ld_g = vc * 2;
+  const int64_t ld_hw = p.d * 2, ld_g = p.ld_v * 2;
   return p.d % 32 == 0 && window_ok(257, ld_hw) && window_ok(257, ld_g) &&      // K-contiguous tiles
          window_ok(vc, ld_hw) && window_ok(nc, ld_hw) && window_ok(nc, ld_g);   // K over memory rows
 }
@@ -94,11 +94,18 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   // Backward staging: a fixed-size G tile of at most vc x nc 256-tiles.
   const int vc_max = env_int("FLCE_VC_TILES", 128, 1, 4096);
   const int nc_max = env_int("FLCE_NC_TILES", 128, 1, 4096);
-  p.n_vch = (int)ceil_div(p.n_vt, vc_max);
-  p.n_nch = (int)ceil_div(p.n_rb, nc_max);
-  p.vc_tiles = (int)ceil_div(p.n_vt, p.n_vch);
-  p.nc_tiles = (int)ceil_div(p.n_rb, p.n_nch);
+  // Chunks of the full size plus a remainder, so that launches of full chunks come out in whole rounds of 256
+  // workgroups (128 tiles times any even tile count); an even split only when the remainder would be a sliver.
+  auto chunking = [](int tiles, int cmax, int& n_chunks, int& chunk) {
+    n_chunks = (int)ceil_div(tiles, cmax);
+    const int rem = tiles - (n_chunks - 1) * cmax;
+    chunk = (n_chunks == 1 || rem * 4 >= cmax) ? std::min(tiles, cmax) : (int)ceil_div(tiles, n_chunks);
+  };
+  chunking(p.n_vt, vc_max, p.n_vch, p.vc_tiles);
+  chunking(p.n_rb, nc_max, p.n_nch, p.nc_tiles);
   const int64_t vc_pad = (int64_t)p.vc_tiles * TILE, nc_pad = (int64_t)p.nc_tiles * TILE;
+  p.ld_v = vc_pad + 64;
+  p.ld_n = nc_pad + 64;
   p.fast = fast_loop_ok(p);
   p.hkr = p.fast && window_ok(d, p.npad * 2);
   p.fwd_bytes = fwd_fixed + (p.hkr ? align_up(d * p.npad * p.esize, ALIGN) : 0);
@@ -108,11 +115,11 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   p.off_tgt = o;    o = align_up(o + p.npad * 4, ALIGN);
   p.off_lsec = o;   o = align_up(o + p.npad * 4, ALIGN);
   p.off_gamc = o;   o = align_up(o + p.npad * 4, ALIGN);
-  p.off_G = o;      o = align_up(o + nc_pad * vc_pad * p.esize, ALIGN);
+  p.off_G = o;      o = align_up(o + nc_pad * p.ld_v * p.esize, ALIGN);
   // K-contiguous copies, only for main loops that cannot read an operand across memory rows
   p.off_HT = o;     if (!p.fast || p.hkr) o = align_up(o + d * p.npad * p.esize, ALIGN);
-  p.off_WT = o;     if (!p.fast) o = align_up(o + d * vc_pad * p.esize, ALIGN);
-  p.off_GT = o;     if (!p.fast) o = align_up(o + nc_pad * vc_pad * p.esize, ALIGN);
+  p.off_WT = o;     if (!p.fast) o = align_up(o + d * p.ld_v * p.esize, ALIGN);
+  p.off_GT = o;     if (!p.fast) o = align_up(o + vc_pad * p.ld_n * p.esize, ALIGN);
   p.off_dHacc = o;  if (p.n_vch > 1) o = align_up(o + N * d * 4, ALIGN);
   p.off_dWacc = o;  if (p.n_nch > 1) o = align_up(o + vc_pad * d * 4, ALIGN);
   // Split-K for launches with too few output tiles to occupy the CUs (small N or small d): the K
@@ -321,19 +328,19 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
   auto slice_len = [](int k_elems, int n_split) { return (int)ceil_div(ceil_div(k_elems, TILE), n_split) * TILE; };
   // argument blocks of the three steps of chunk (vc, nc); `Gb` is the staging buffer of that chunk
   auto chunk_vt = [&](int vc, int& vt0, int& n_vt) {
-    vt0 = (int)((int64_t)vc * p.n_vt / p.n_vch);
-    n_vt = (int)((int64_t)(vc + 1) * p.n_vt / p.n_vch) - vt0;
+    vt0 = vc * p.vc_tiles;
+    n_vt = std::min(p.vc_tiles, p.n_vt - vt0);
   };
   auto chunk_nt = [&](int nc, int& nt0, int& n_nt) {
-    nt0 = (int)((int64_t)nc * p.n_rb / p.n_nch);
-    n_nt = (int)((int64_t)(nc + 1) * p.n_rb / p.n_nch) - nt0;
+    nt0 = nc * p.nc_tiles;
+    n_nt = std::min(p.nc_tiles, p.n_rb - nt0);
   };
   auto recompute_args = [&](int vc, int nc, T* Gb) {
     int vt0, n_vt, nt0, n_nt;
     chunk_vt(vc, vt0, n_vt);
     chunk_nt(nc, nt0, n_nt);
     return RecomputeArgs<T>{Hc, HT, static_cast<const T*>(W), tgt_c, lse_c, hdr, npad, d, V, nt0, n_nt, vt0, n_vt,
-                            Gb, vc_pad, GT, nc_pad, gam_c, 1.f - rows.eps, rows.eps / (float)slice.V_total};
+                            Gb, p.ld_v, GT, p.ld_n, gam_c, 1.f - rows.eps, rows.eps / (float)slice.V_total};
   };
   // dW[vocab chunk] += G^T . Hc[row chunk]   (contraction over the compact rows of the chunk)
   auto dw_args = [&](int vc, int nc, const T* Gb) {
@@ -344,12 +351,12 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     if (nc > 0) flags |= READ_ACC;
     flags |= (nc + 1 < p.n_nch) ? WRITE_ACC : WRITE_OUT;
     if constexpr (L::TRANSPOSING)
-      return ContractArgs<T>{Hc + (int64_t)nt0 * TILE * d, d, npad - nt0 * TILE, d, Gb, vc_pad, n_nt * TILE,
+      return ContractArgs<T>{Hc + (int64_t)nt0 * TILE * d, d, npad - nt0 * TILE, d, Gb, p.ld_v, n_nt * TILE,
                              n_nt * TILE, nt0 * TILE, n_mt, n_vt, dWacc, vt0 * TILE, static_cast<T*>(dW), vt0 * TILE,
                              V, flags, hdr, rowmap, grad_loss, mean, p.split_dw,
                              slice_len(n_nt * TILE, p.split_dw), partial, vc_pad * d};
     else
-      return ContractArgs<T>{HT + (int64_t)nt0 * TILE, p.npad, 0, d, GT, nc_pad, n_vt * TILE, n_nt * TILE,
+      return ContractArgs<T>{HT + (int64_t)nt0 * TILE, p.npad, 0, d, GT, p.ld_n, n_vt * TILE, n_nt * TILE,
                              nt0 * TILE, n_mt, n_vt, dWacc, vt0 * TILE, static_cast<T*>(dW), vt0 * TILE, V, flags,
                              hdr, rowmap, grad_loss, mean, p.split_dw, slice_len(n_nt * TILE, p.split_dw), partial,
                              vc_pad * d};
@@ -363,12 +370,12 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     if (vc > 0) flags |= READ_ACC;
     flags |= (vc + 1 < p.n_vch) ? WRITE_ACC : WRITE_OUT;
     if constexpr (L::TRANSPOSING)
-      return ContractArgs<T>{static_cast<const T*>(W) + (int64_t)vt0 * TILE * d, d, V - vt0 * TILE, d, Gb, vc_pad,
+      return ContractArgs<T>{static_cast<const T*>(W) + (int64_t)vt0 * TILE * d, d, V - vt0 * TILE, d, Gb, p.ld_v,
                              n_nt * TILE, n_vt * TILE, 0, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH), nt0 * TILE, npad,
                              flags, hdr, rowmap, grad_loss, mean, p.split_dh, slice_len(n_vt * TILE, p.split_dh),
                              partial - (int64_t)nt0 * TILE * d, nc_pad * d};
     else
-      return ContractArgs<T>{WT, vc_pad, 0, d, Gb, vc_pad, n_nt * TILE, n_vt * TILE, 0, n_mt, n_nt, dHacc, 0,
+      return ContractArgs<T>{WT, p.ld_v, 0, d, Gb, p.ld_v, n_nt * TILE, n_vt * TILE, 0, n_mt, n_nt, dHacc, 0,
                              static_cast<T*>(dH), nt0 * TILE, npad, flags, hdr, rowmap, grad_loss, mean, p.split_dh,
                              slice_len(n_vt * TILE, p.split_dh), partial - (int64_t)nt0 * TILE * d, nc_pad * d};
   };
@@ -377,10 +384,10 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     int vt0, n_vt;
     chunk_vt(vc, vt0, n_vt);
     if constexpr (!L::TRANSPOSING) {
-      // W^T chunk [d][vc_pad]: K-contiguous operand of the dH contraction
+      // W^T chunk [d][ld_v]: K-contiguous operand of the dH contraction
       ProfScope ps(FLCE_PROF_BWD_PREP, st);
       transpose_pad_kernel<U><<<dim3((unsigned)(n_vt * TILE / 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
-          static_cast<const U*>(W), d, V, vt0 * TILE, d, reinterpret_cast<U*>(WT), vc_pad, n_vt * TILE);
+          static_cast<const U*>(W), d, V, vt0 * TILE, d, reinterpret_cast<U*>(WT), p.ld_v, n_vt * TILE);
     }
     for (int nc = 0; nc < p.n_nch; ++nc) {
       {

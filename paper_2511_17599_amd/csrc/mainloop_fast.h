@@ -28,7 +28,7 @@
 //     stream.
 //
 // Requires the K extent to be a multiple of 32 elements and offsets inside one tile's
-// address window within 2^31 bytes; the generic loop in tile_mma.h covers everything else.
+// address window within 2^32 bytes (unsigned 32-bit buffer offsets); the generic loop in tile_mma.h covers everything else.
 #pragma once
 #include "tile_mma.h"
 
