@@ -6,7 +6,10 @@
  * gradients dH, dW, without ever storing the N x V logits (the paper's
  * Section 3.2: the direct loss of Eq. 3, the streaming forward of Alg. 1, the
  * recompute backward of Alg. 2 / Eq. 4 / Eq. 5, and the window strategy with
- * its merging epilogue of Section 3.2.1).
+ * its merging epilogue of Section 3.2.1).  Further entry points cover the
+ * partial-gradient variant (Alg. 3 / Alg. 4), a per-row loss with per-row
+ * upstream gradients and label smoothing, and vocabulary-sliced calls for
+ * tensor / sequence parallel layouts.
  *
  * Conventions common to every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller, row-major and
@@ -27,7 +30,8 @@
  *     stream) and the calls return without synchronising.  Outputs are fully
  *     overwritten.  Results are bit-identical from run to run for the same
  *     inputs, shapes and tuning environment: no floating-point atomics, every
- *     sum has a fixed order.
+ *     sum has a fixed order.  Only kernels are enqueued (no allocation, memset or
+ *     synchronisation), so a sequence of calls can be captured into a HIP graph.
  *   - Host-detectable errors (null pointer, non-positive size, d not a multiple
  *     of 8, workspace too small, unknown enum) return a status and launch
  *     nothing.  A failing HIP runtime call returns FLCE_ERR_HIP.  Nothing is
@@ -52,7 +56,7 @@ typedef enum {
   FLCE_ERR_BAD_SHAPE = 2,    /* N, d or V <= 0, d % 8 != 0, sizes beyond 2^31-1 rows */
   FLCE_ERR_WORKSPACE = 3,    /* workspace null, misaligned or smaller than required */
   FLCE_ERR_TARGET_RANGE = 4, /* a counted target was outside [0, V) (device-detected) */
-  FLCE_ERR_UNSUPPORTED = 5,  /* reserved (e.g. reduction "none") */
+  FLCE_ERR_UNSUPPORTED = 5,  /* reserved */
   FLCE_ERR_HIP = 6           /* a HIP runtime call failed */
 } flce_status;
 
