@@ -333,3 +333,33 @@ def test_per_row_losses_and_gradients(monkeypatch, dtype, eps, generic):
     assert eH <= tol["grad"] and eW <= tol["grad"]
     raw = s.dH.view(torch.int16 if dtype == "bf16" else torch.int32).cpu().numpy()
     assert not raw[~f["valid"]].any()
+
+
+def _random_cases(n, seed):
+    r = np.random.default_rng(seed)
+    cases = []
+    for k in range(n):
+        dtype = "bf16" if r.random() < 0.75 else "f32"
+        d = int(r.choice([8, 24, 32, 64, 96, 160, 256, 320, 512]))
+        N = int(r.integers(1, 1400))
+        V = int(r.integers(1, 3000))
+        cases.append(dict(
+            wl=custom(f"rand{k}", N, d, V, dtype, 500 + k, targets="zipf" if r.random() < 0.4 else "uniform",
+                      ignore_frac=float(r.choice([0.0, 0.05, 0.5, 0.95])), reduction="sum" if r.random() < 0.4 else "mean",
+                      w_std=float(r.choice([0.02, 0.3]))),
+            env=dict(FLCE_WINDOWS=str(int(r.choice([0, 1, 2, 7]))), FLCE_VC_TILES=str(int(r.choice([1, 2, 3, 128]))),
+                     FLCE_NC_TILES=str(int(r.choice([1, 2, 128]))), FLCE_SPLITK_DH=str(int(r.choice([0, 0, 2, 3]))),
+                     FLCE_SPLITK_DW=str(int(r.choice([0, 0, 2])))),
+            grad_loss=float(r.choice([1.0, -0.5, 3.0]))))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_cases(24, 2024), ids=lambda c: c["wl"].name)
+def test_seeded_random_shapes_and_plans(monkeypatch, case):
+    """A fixed, seeded set of arbitrary shapes (ragged everywhere, d with and without the tuned loop), target
+    mixes and launch plans (windows, chunk sizes, K splits)."""
+    for k, v in case["env"].items():
+        monkeypatch.setenv(k, v)
+    wl = case["wl"]
+    print(f"[plan] {case['env']}", flush=True)
+    check_against_oracle(wl, I.make_inputs(wl), grad_loss=case["grad_loss"])
