@@ -239,7 +239,7 @@ def main():
 
     rows = args.oracle_rows
     if rows is None:
-        rows = max(16, min(wl.N, int(8.0e12 / (6.0 * wl.d * wl.V))))     # ~10-20 s of fp64 work
+        rows = max(16, min(wl.N, int(1.2e13 / (6.0 * wl.d * wl.V))))     # ~10-20 s of fp64 work
     base = None
     if rows > 0:
         base, f = cpu_baseline(wl, x, min(rows, wl.N))
