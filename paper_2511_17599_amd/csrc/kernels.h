@@ -17,6 +17,11 @@
 //             splitk_reduce_kernel (fixed-order sum of K slices when a contraction
 //             launch would otherwise leave most CUs idle)
 //   Alg. 3/4: the forward and the backward above with Gamma = 1, then scale_kernel
+//   per row : merge_rows_kernel writes one loss per row (label smoothing: colsum_* and
+//             mean_logit_kernel give mean_v Z_iv), recompute_kernel<.., PER_ROW> scales each
+//             row of G by that row's upstream gradient
+//   slices  : the same kernels on rows [v_begin, v_begin + V) of the vocabulary
+//             (classify_target_in_slice); merge_rows_partial_kernel hands out (m, a, z_target)
 #pragma once
 #include <type_traits>
 
