@@ -131,7 +131,7 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
     // split has to win by 5 %.
     int best = 1;
     double best_score = 0.0;
-    for (int sp = 1; sp <= 8 && (sp == 1 || k_tiles / sp >= 4); ++sp) {
+    for (int sp = 1; sp <= 8 && (sp == 1 || k_tiles / sp >= 2); ++sp) {
       const int64_t wg = tiles * sp;
       const double fill = (double)wg / (double)(ceil_div(wg, NUM_CU) * NUM_CU);
       const double score = fill / (1.0 + (4.8 / (double)k_tiles) * (sp - 1));
