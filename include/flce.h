@@ -39,6 +39,19 @@
  *   - Re-entrant: all state lives in the caller's workspace.  Concurrent calls
  *     must use distinct workspaces.
  *   - n_valid == 0 gives loss 0 and zero gradients (both reductions).
+ *
+ * Tuning environment (read at every call, by flce_workspace_bytes too, so it must not change
+ * between sizing a workspace and using it; defaults suit MI355X; results stay within the
+ * tolerances for any setting but their rounding, and the bit pattern, depend on it):
+ *   FLCE_WINDOWS    vocabulary windows of the forward (Section 3.2.1); 0 / unset = automatic
+ *                   (at least 4, enough row block x window workgroups to cover 256 CUs).
+ *   FLCE_VC_TILES   largest vocabulary chunk of the backward, in 256-row tiles (default 128).
+ *   FLCE_NC_TILES   largest token chunk of the backward, in 256-row tiles (default 128).
+ *                   The staging buffer for G holds one chunk pair: at most VC x NC tiles.
+ *   FLCE_SPLITK_DH, FLCE_SPLITK_DW
+ *                   K slices of the dH / dW contraction launches; 0 / unset = automatic
+ *                   (split only when a launch has too few output tiles for the CUs).
+ *   FLCE_GENERIC    1 = use the generic main loop also where the tuned bf16 loop applies.
  */
 #ifndef FLCE_H_
 #define FLCE_H_
