@@ -36,13 +36,18 @@
  *     of 8, workspace too small, unknown enum) return a status and launch
  *     nothing.  A failing HIP runtime call returns FLCE_ERR_HIP.  Nothing is
  *     printed, nothing throws.
- *   - Re-entrant: all state lives in the caller's workspace.  Concurrent calls
- *     must use distinct workspaces.
+ *   - All state of a computation lives in the caller's workspace; concurrent calls must use
+ *     distinct workspaces.  Process-wide state is limited to: the tuning knobs below (read once),
+ *     a per-device "kernel attributes set" flag, and the optional launch profiler
+ *     (flce_profile_*); all three are guarded by mutexes.
  *   - n_valid == 0 gives loss 0 and zero gradients (both reductions).
  *
- * Tuning environment (read at every call, by flce_workspace_bytes too, so it must not change
- * between sizing a workspace and using it; defaults suit MI355X; results stay within the
- * tolerances for any setting but their rounding, and the bit pattern, depend on it):
+ * Tuning environment.  Read ONCE per process, by the first call that needs a launch plan
+ * (flce_workspace_bytes included), and fixed from then on, so the plan a workspace was sized
+ * for is the plan that runs; flce_tuning_reload() reads it again (tests use it; do not call it
+ * between sizing a workspace and using it, or while another thread is inside the library).
+ * Defaults suit MI355X; results stay within the tolerances for any setting but their
+ * rounding, and the bit pattern, depend on it:
  *   FLCE_WINDOWS    vocabulary windows of the forward (Section 3.2.1); 0 / unset = automatic
  *                   (at least 4, enough row block x window workgroups to cover 256 CUs).
  *   FLCE_VC_TILES   largest vocabulary chunk of the backward, in 256-row tiles (default 128).
@@ -81,6 +86,9 @@ typedef enum { FLCE_REDUCE_MEAN = 0, FLCE_REDUCE_SUM = 1 } flce_reduction;
 
 /* Library version, "major.minor.patch". Host call. */
 const char* flce_version(void);
+
+/* Reads the FLCE_* tuning variables again (see the top of this file). Host call. */
+void flce_tuning_reload(void);
 
 /* Static, human-readable name of a status code. Host call. */
 const char* flce_status_string(flce_status s);

@@ -18,7 +18,7 @@ FLCE_ERR_TARGET_RANGE, FLCE_ERR_UNSUPPORTED, FLCE_ERR_HIP = 4, 5, 6
 FLCE_DTYPE_BF16, FLCE_DTYPE_F32 = 0, 1
 FLCE_REDUCE_MEAN, FLCE_REDUCE_SUM = 0, 1
 
-EXPORTS = ("flce_version", "flce_status_string", "flce_workspace_bytes", "flce_forward", "flce_backward",
+EXPORTS = ("flce_version", "flce_tuning_reload", "flce_status_string", "flce_workspace_bytes", "flce_forward", "flce_backward",
            "flce_forward_with_grads", "flce_scale", "flce_forward_rows", "flce_backward_rows", "flce_forward_partial", "flce_merge_workspace_bytes",
            "flce_merge_partials", "flce_backward_partial", "flce_last_device_status", "flce_profile_enable",
            "flce_profile_collect")
@@ -37,6 +37,8 @@ def lib():
         c = ctypes
         L.flce_version.restype = c.c_char_p
         L.flce_version.argtypes = []
+        L.flce_tuning_reload.restype = None
+        L.flce_tuning_reload.argtypes = []
         L.flce_status_string.restype = c.c_char_p
         L.flce_status_string.argtypes = [c.c_int]
         L.flce_workspace_bytes.restype = c.c_size_t
@@ -105,6 +107,10 @@ def _stream(s):
 
 def flce_version():
     return lib().flce_version().decode()
+
+
+def flce_tuning_reload():
+    lib().flce_tuning_reload()
 
 
 def flce_status_string(status):

@@ -30,6 +30,33 @@ int env_int(const char* name, int dflt, int lo, int hi) {
   return (int)v;
 }
 
+// The tuning knobs of the launch plan.  Read from the environment once, when the first call needs them, and
+// fixed for the process from then on (flce_tuning_reload reads them again): a plan never changes between the
+// sizing of a workspace and its use, and no call touches the environment afterwards.
+struct Tuning {
+  int windows, vc_tiles, nc_tiles, splitk_dh, splitk_dw, generic;
+};
+std::mutex g_tuning_mu;
+bool g_tuning_loaded = false;
+Tuning g_tuning;
+
+Tuning read_tuning_from_env() {
+  Tuning t;
+  t.windows = env_int("FLCE_WINDOWS", 0, 0, 1 << 16);
+  t.vc_tiles = env_int("FLCE_VC_TILES", 128, 1, 4096);
+  t.nc_tiles = env_int("FLCE_NC_TILES", 128, 1, 4096);
+  t.splitk_dh = env_int("FLCE_SPLITK_DH", 0, 0, 16);
+  t.splitk_dw = env_int("FLCE_SPLITK_DW", 0, 0, 16);
+  t.generic = env_int("FLCE_GENERIC", 0, 0, 1);
+  return t;
+}
+
+Tuning tuning() {
+  std::lock_guard<std::mutex> lk(g_tuning_mu);
+  if (!g_tuning_loaded) { g_tuning = read_tuning_from_env(); g_tuning_loaded = true; }
+  return g_tuning;
+}
+
 struct Plan {
   int64_t N, d, V;
   int esize;
@@ -52,17 +79,17 @@ struct Plan {
 // The tuned bf16 loop needs K extents that are multiples of 32 elements and every tile's address
 // window within reach of a buffer descriptor: offsets and the record count are unsigned 32-bit, and
 // the zero-filled overshoot of a last K stage (up to 32 rows) must not wrap 2^32.
-// FLCE_GENERIC=1 forces the generic loop everywhere.
+// The `generic` knob forces the generic loop everywhere.
 bool window_ok(int64_t k_rows, int64_t ld_bytes) { return (k_rows + 32) * ld_bytes < ((int64_t)1 << 32); }
-bool fast_loop_ok(const Plan& p) {
-  if (p.esize != 2 || env_int("FLCE_GENERIC", 0, 0, 1)) return false;
+bool fast_loop_ok(const Plan& p, const Tuning& tn) {
+  if (p.esize != 2 || tn.generic) return false;
   const int64_t vc = (int64_t)p.vc_tiles * TILE, nc = (int64_t)p.nc_tiles * TILE;
   const int64_t ld_hw = p.d * 2, ld_g = p.ld_v * 2;
   return p.d % 32 == 0 && window_ok(257, ld_hw) && window_ok(257, ld_g) &&      // K-contiguous tiles
          window_ok(vc, ld_hw) && window_ok(nc, ld_hw) && window_ok(nc, ld_g);   // K over memory rows
 }
 
-bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
+bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p, bool allow_h_copy = true) {
   if (N <= 0 || d <= 0 || V <= 0 || (d % 8) != 0) return false;
   if (N > 0x7FFFFF00ll || V > 0x7FFFFF00ll || d > (1 << 24)) return false;
   if (dt != FLCE_DTYPE_BF16 && dt != FLCE_DTYPE_F32) return false;
@@ -75,7 +102,8 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   // Windows (Section 3.2.1): enough (row block, window) workgroups to cover the CUs.
   // At least 4, so that the 32 workgroups resident on one XCD are 8 row blocks x 4 windows and
   // share both operands through that XCD's L2 (one window would stream every H block from HBM).
-  int win = env_int("FLCE_WINDOWS", 0, 0, 1 << 16);
+  const Tuning tn = tuning();
+  int win = tn.windows;
   if (win == 0) win = (int)std::max<int64_t>(4, ceil_div(NUM_CU, p.n_rb));
   if (win > p.n_vt) win = p.n_vt;
   p.n_win = win;
@@ -92,8 +120,8 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   const int64_t fwd_fixed = o;
 
   // Backward staging: a fixed-size G tile of at most vc x nc 256-tiles.
-  const int vc_max = env_int("FLCE_VC_TILES", 128, 1, 4096);
-  const int nc_max = env_int("FLCE_NC_TILES", 128, 1, 4096);
+  const int vc_max = tn.vc_tiles;
+  const int nc_max = tn.nc_tiles;
   // Chunks of the full size plus a remainder, so that launches of full chunks come out in whole rounds of 256
   // workgroups (128 tiles times any even tile count); an even split only when the remainder would be a sliver.
   auto chunking = [](int tiles, int cmax, int& n_chunks, int& chunk) {
@@ -106,8 +134,8 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
   const int64_t vc_pad = (int64_t)p.vc_tiles * TILE, nc_pad = (int64_t)p.nc_tiles * TILE;
   p.ld_v = vc_pad + 64;
   p.ld_n = nc_pad + 64;
-  p.fast = fast_loop_ok(p);
-  p.hkr = p.fast && window_ok(d, p.npad * 2);
+  p.fast = fast_loop_ok(p, tn);
+  p.hkr = allow_h_copy && p.fast && window_ok(d, p.npad * 2);
   p.fwd_bytes = fwd_fixed + (p.hkr ? align_up(d * p.npad * p.esize, ALIGN) : 0);
   o = ALIGN;
   p.off_Hc = o;     o = align_up(o + d * p.npad * p.esize, ALIGN);
@@ -139,8 +167,8 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p) {
     }
     return best;
   };
-  p.split_dh = env_int("FLCE_SPLITK_DH", 0, 0, 16);
-  p.split_dw = env_int("FLCE_SPLITK_DW", 0, 0, 16);
+  p.split_dh = tn.splitk_dh;
+  p.split_dw = tn.splitk_dw;
   if (p.split_dh == 0) p.split_dh = auto_split(p.nc_tiles * n_mt, p.vc_tiles);
   if (p.split_dw == 0) p.split_dw = auto_split(p.vc_tiles * n_mt, p.nc_tiles);
   p.split_dh = (int)std::min<int64_t>(p.split_dh, p.vc_tiles);
@@ -192,8 +220,12 @@ hipError_t allow_big_lds(K kernel, int bytes) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
+// The kernels of one (storage type, main loop) pair need the large dynamic LDS allowance; it is a property of
+// the loaded code object on a device, so it is set once per device and pair, not per call.
+constexpr int MAX_DEVICES = 64;
+
 template <typename T, typename L>
-hipError_t prepare_kernels() {
+hipError_t set_lds_allowances() {
   hipError_t e;
   if ((e = allow_big_lds(fwd_tiles_kernel<T, L, false>, L::LDS)) != hipSuccess) return e;
   if ((e = allow_big_lds(recompute_kernel<T, L, false>, L::LDS)) != hipSuccess) return e;
@@ -202,13 +234,26 @@ hipError_t prepare_kernels() {
     if ((e = allow_big_lds(fwd_tiles_kernel<T, L, true>, L::LDS)) != hipSuccess) return e;
     if ((e = allow_big_lds(recompute_kernel<T, L, true>, L::LDS)) != hipSuccess) return e;
     if ((e = allow_big_lds(recompute_kernel<T, L, true, true>, L::LDS)) != hipSuccess) return e;
-  }
-  if constexpr (L::TRANSPOSING) {
     if ((e = allow_big_lds(contract_kernel<T, L, OPS_DH_TR>, L::LDS)) != hipSuccess) return e;
     if ((e = allow_big_lds(contract_kernel<T, L, OPS_DW_TR>, L::LDS)) != hipSuccess) return e;
   } else {
     if ((e = allow_big_lds(contract_kernel<T, L, OPS_KC>, L::LDS)) != hipSuccess) return e;
   }
+  return hipSuccess;
+}
+
+template <typename T, typename L>
+hipError_t prepare_kernels() {
+  static std::mutex mu;
+  static bool done[MAX_DEVICES] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(mu);
+  if (done[dev]) return hipSuccess;
+  if ((e = set_lds_allowances<T, L>()) != hipSuccess) return e;
+  done[dev] = true;
   return hipSuccess;
 }
 
@@ -434,7 +479,13 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 extern "C" {
 
-const char* flce_version(void) { return "0.1.0"; }
+const char* flce_version(void) { return "0.2.0"; }
+
+void flce_tuning_reload(void) {
+  std::lock_guard<std::mutex> lk(flce::g_tuning_mu);
+  flce::g_tuning = flce::read_tuning_from_env();
+  flce::g_tuning_loaded = true;
+}
 
 const char* flce_status_string(flce_status s) {
   switch (s) {
@@ -459,7 +510,7 @@ static flce_status forward_impl(const void* H, const void* W, const int64_t* tar
                                 int64_t V, int64_t ignore_index, flce_reduction reduction, flce_dtype dt,
                                 float* loss_out, float* lse_out, void* workspace, size_t workspace_bytes,
                                 void* hip_stream, flce::Slice slice, float* m_out, float* a_out, float* zt_out,
-                                flce::PerRow rows = flce::PerRow{nullptr, nullptr, 0.f}) {
+                                flce::PerRow rows = flce::PerRow{nullptr, nullptr, 0.f}, bool allow_h_copy = true) {
   const bool partial = m_out || a_out || zt_out;
   if (!H || !W || !targets) return FLCE_ERR_BAD_ARG;
   if (partial ? (!m_out || !a_out || !zt_out) : ((!loss_out && !rows.loss_rows_out) || !lse_out))
@@ -468,7 +519,7 @@ static flce_status forward_impl(const void* H, const void* W, const int64_t* tar
   if (reduction != FLCE_REDUCE_MEAN && reduction != FLCE_REDUCE_SUM) return FLCE_ERR_BAD_ARG;
   if (dt != FLCE_DTYPE_BF16 && dt != FLCE_DTYPE_F32) return FLCE_ERR_BAD_ARG;
   flce::Plan p;
-  if (!flce::make_plan(N, d, V, dt, p)) return FLCE_ERR_BAD_SHAPE;
+  if (!flce::make_plan(N, d, V, dt, p, allow_h_copy)) return FLCE_ERR_BAD_SHAPE;
   if (slice.v_begin < 0 || slice.v_begin + V > slice.V_total) return FLCE_ERR_BAD_SHAPE;
   if (!flce::aligned16(H) || !flce::aligned16(W)) return FLCE_ERR_BAD_ARG;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < (size_t)p.fwd_bytes)

@@ -375,7 +375,7 @@ __global__ __launch_bounds__(256) void mean_logit_kernel(const T* __restrict__ H
 }
 
 // The window merge of a call that covers one vocabulary slice: the slice's (m, a, z_target) per row,
-// to be merged with the other slices' later (Section 3.3, tensor parallelism).
+// to be merged with the other slices' later (Section 3.2, "Model Parallelism": tensor parallelism).
 __global__ __launch_bounds__(256) void merge_rows_partial_kernel(const float* __restrict__ part, int n_win,
                                                                  int64_t npad, int N, float* __restrict__ m_out,
                                                                  float* __restrict__ a_out,

@@ -117,19 +117,14 @@ class _RowLosses(torch.autograd.Function):
 def linear_cross_entropy(H, W, targets, ignore_index=-100, reduction="mean", label_smoothing=0.0):
     """Cross-entropy of softmax(H . W^T) against `targets` without the logits tensor.
 
-    reduction: "mean" (over rows whose target is not `ignore_index`), "sum" or "none".  With label smoothing the
-    row losses come from the per-row call and the mean / sum is taken over them here.
+    reduction: "mean" (over rows whose target is not `ignore_index`), "sum" or "none".  Label smoothing comes
+    with one loss per row only (reduction="none", the library's per-row call): reduce the rows with torch as
+    needed, autograd hands the per-row upstream gradients back to the library.
     """
     if reduction not in ("mean", "sum", "none"):
         raise ValueError("reduction must be 'mean', 'sum' or 'none'")
-    if reduction != "none" and label_smoothing == 0.0:
+    if reduction != "none":
+        if label_smoothing != 0.0:
+            raise ValueError("label smoothing is available with reduction='none' only")
         return _ScalarLoss.apply(H, W, targets, int(ignore_index), reduction)
-    rows = _RowLosses.apply(H, W, targets, int(ignore_index), float(label_smoothing))
-    if reduction == "none":
-        return rows
-    total = rows.sum()
-    if reduction == "sum":
-        return total
-    V = W.shape[0]
-    counted = ((targets != ignore_index) & (targets >= 0) & (targets < V)).sum()
-    return total / counted.clamp_min(1)
+    return _RowLosses.apply(H, W, targets, int(ignore_index), float(label_smoothing))

@@ -8,7 +8,10 @@ the oracle is evaluated on sampled outputs it can compute one by one:
 and dW through properties that hold at any size: its column sums vanish (every row of G
 sums to zero) up to the rounding of its entries and <dH, H> = <dW, W> (both equal sum_iv G_iv Z_iv).  Where affordable
 (all but the long-sequence shape) the oracle's lse of EVERY row is computed too, which gives exact dW rows
-for a sample of vocabulary ids (hot, cold, tile-edge, last).
+for a sample of vocabulary ids (hot, cold, tile-edge, last); at the long-sequence shape the same dW rows are
+computed with the device's lse, validated on the row sample first ("borrowed lse").
+Two points of the paper's own evaluation grid (Table 1: d = 4096, power-of-two vocabularies) are checked the same
+way, the small one (four row blocks x 64 vocabulary windows, the regime Section 3.2.1 is about) in full.
 """
 import time
 
@@ -26,12 +29,9 @@ from paper_2511_17599_amd.runner import session_for, to_host_f64   # noqa: E402
 
 
 @pytest.fixture(autouse=True)
-def _need_gpu(monkeypatch):
+def _need_gpu():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    for k in ("FLCE_WINDOWS", "FLCE_VC_TILES", "FLCE_NC_TILES", "FLCE_GENERIC", "FLCE_SPLITK_DH", "FLCE_SPLITK_DW"):
-        monkeypatch.delenv(k, raising=False)
-    yield
 
 
 def sample_rows(wl, y, k, seed):
@@ -109,20 +109,36 @@ def run_fullsize(name, n_rows, full_lse):
     print(f"       dW column sums: largest is {col:.3f} of its rounding bound (max |dW| {mx:.3e}); <dH,H> {lhs:.6e} <dW,W> {rhs:.6e}", flush=True)
     del dW
 
+    # dW rows of a sample of vocabulary ids (hot, first, tile edges, last tile, last, random cold ones), element by
+    # element.  Row v of dW needs G_iv of EVERY token, hence every row's lse: the oracle's own where 3*N*d*V fp64
+    # multiply-adds are affordable, otherwise the device's lse, which the row sample above has just validated
+    # against the oracle ("oracle with borrowed lse": exp(z - lse) is the only place it enters).
+    Hd = I.to_f64(x["H"])
     if full_lse:
         t1 = time.time()
-        f = O.forward(I.to_f64(x["H"]), Wd, y, wl.ignore_index, wl.reduction, block_rows=512)
+        f = O.forward(Hd, Wd, y, wl.ignore_index, wl.reduction, block_rows=512)
         print(f"       oracle lse of all rows: {time.time() - t1:.1f} s", flush=True)
         assert abs(got - f["loss"]) <= 2e-3 * abs(f["loss"])
         assert np.abs(lse_g - f["lse"]).max() <= 2e-3 * np.abs(f["lse"]).max()
-        hot = np.bincount(y[valid], minlength=wl.V).argsort()[::-1][:4]
-        ids = np.unique(np.concatenate([hot, [0, 255, 256, wl.V - 257, wl.V - 256, wl.V - 1],
-                                        np.random.default_rng(5).integers(0, wl.V, 6)]))
-        dW_o = O.dW_rows(I.to_f64(x["H"]), Wd[ids], ids, y, f["lse"], gam, wl.ignore_index, V=wl.V)
-        dW_g = s.dW[torch.from_numpy(ids).to(s.dW.device)].float().cpu().numpy().astype(np.float64)
-        err = np.abs(dW_g - dW_o).max() / np.abs(dW_o).max()
-        print(f"       sampled dW rows err {err:.2e}", flush=True)
-        assert err <= 2e-2
+        lse_all, label = f["lse"], "oracle lse"
+    else:
+        lse_all, label = lse_mix, "oracle with borrowed lse"
+    hot = np.bincount(y[valid], minlength=wl.V).argsort()[::-1][:4]
+    ids = np.unique(np.concatenate([hot, [0, 255, 256, wl.V - 257, wl.V - 256, wl.V - 1],
+                                    np.random.default_rng(5).integers(0, wl.V, 6)]) % wl.V)
+    dW_o = O.dW_rows(Hd, Wd[ids], ids, y, lse_all, gam, wl.ignore_index, V=wl.V)
+    dW_g = s.dW[torch.from_numpy(ids).to(s.dW.device)].float().cpu().numpy().astype(np.float64)
+    err = np.abs(dW_g - dW_o).max() / np.abs(dW_o).max()
+    # The global norm is set by the hottest rows (Zipf targets: a few ids own most of max|dW|), so the cold rows
+    # are also judged each against its own largest entry.
+    per_row = np.abs(dW_g - dW_o).max(axis=1) / np.maximum(np.abs(dW_o).max(axis=1), 1e-300)
+    counts = np.bincount(y[valid], minlength=wl.V)[ids]
+    cold = counts <= np.median(np.bincount(y[valid], minlength=wl.V)) + 1
+    print(f"       sampled dW rows ({label}): err {err:.2e} of max|ref|; per-row normalised: worst {per_row.max():.2e}, "
+          f"worst cold row {per_row[cold].max() if cold.any() else 0.0:.2e} ({int(cold.sum())} cold of {len(ids)})",
+          flush=True)
+    assert err <= 2e-2
+    assert per_row.max() <= 5e-2
 
 
 def test_llama3_8b_full_size():
@@ -135,6 +151,34 @@ def test_large_vocab_full_size():
 
 def test_long_seq_full_size():
     run_fullsize("long_seq", 24, full_lse=False)
+
+
+def test_paper_grid_point_small_rows_many_windows():
+    """Table 1's smallest point: N = 1024 rows are four row blocks, so the forward cuts the vocabulary into 64
+    windows (Section 3.2.1).  Small enough for the whole two-stage oracle: every lse, dH and dW element."""
+    wl = I.Workload("grid_1024_32768", 1024, 4096, 32768, "bf16", "uniform", ignore_frac=0.0, seed=2201)
+    print(f"[case] paper grid point {wl.name} N={wl.N} d={wl.d} V={wl.V} seed={wl.seed}", flush=True)
+    x = I.make_inputs(wl)
+    s = session_for(wl, x)
+    assert s.forward() == B.FLCE_OK and s.backward() == B.FLCE_OK
+    st, nv = s.device_status()
+    Hd, Wd = I.to_f64(x["H"]), I.to_f64(x["W"])
+    f = O.forward(Hd, Wd, x["y"], wl.ignore_index, wl.reduction)
+    b = O.backward(Hd, Wd, x["y"], wl.ignore_index, wl.reduction)
+    assert st == B.FLCE_OK and nv == f["n_valid"] == wl.N
+    got = float(s.loss.item())
+    assert abs(got - f["loss"]) <= 2e-3 * abs(f["loss"]), (got, f["loss"])
+    assert np.abs(to_host_f64(s.lse) - f["lse"]).max() <= 2e-3 * np.abs(f["lse"]).max()
+    eH = np.abs(to_host_f64(s.dH) - b["dH"]).max() / np.abs(b["dH"]).max()
+    eW = np.abs(to_host_f64(s.dW) - b["dW"]).max() / np.abs(b["dW"]).max()
+    print(f"       loss {got:.6f} vs {f['loss']:.6f}  dH {eH:.2e}  dW {eW:.2e}", flush=True)
+    assert eH <= 2e-2 and eW <= 2e-2
+
+
+def test_paper_grid_point_large_vocabulary():
+    """Table 1's widest vocabulary at N = 4096 (16 row blocks x 16 windows, 1024 vocabulary tiles, 8 chunks)."""
+    wl = I.Workload("grid_4096_262144", 4096, 4096, 262144, "bf16", "uniform", ignore_frac=0.0, seed=2202)
+    run_fullsize(wl, 24, full_lse=True)
 
 
 def test_hidden_states_beyond_2_31_elements():

@@ -18,17 +18,15 @@ from oracle import flce_oracle as O                       # noqa: E402
 from paper_2511_17599_amd import binding as B             # noqa: E402
 from paper_2511_17599_amd import inputs as I              # noqa: E402
 from paper_2511_17599_amd.runner import run_workload      # noqa: E402
+from conftest import set_plan                              # noqa: E402
 
 TOL = {"f32": dict(loss=1e-5, grad=1e-4, lse=2e-6), "bf16": dict(loss=2e-3, grad=2e-2, lse=2e-3)}
 
 
 @pytest.fixture(autouse=True)
-def _need_gpu_and_clean_env(monkeypatch):
+def _need_gpu():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
-    for k in ("FLCE_WINDOWS", "FLCE_VC_TILES", "FLCE_NC_TILES", "FLCE_GENERIC", "FLCE_SPLITK_DH", "FLCE_SPLITK_DW"):
-        monkeypatch.delenv(k, raising=False)
-    yield
 
 
 def nerr(got, ref):
@@ -99,10 +97,7 @@ def test_chunk_and_window_splits(monkeypatch, dtype, generic, windows, vc, nc):
     the backward on a small problem, so the merge and the fixed-order accumulation are exercised;
     for bf16 once with the tuned main loop (operands read in place) and once with the generic one
     (transposed copies)."""
-    monkeypatch.setenv("FLCE_WINDOWS", str(windows))
-    monkeypatch.setenv("FLCE_VC_TILES", str(vc))
-    monkeypatch.setenv("FLCE_NC_TILES", str(nc))
-    monkeypatch.setenv("FLCE_GENERIC", str(generic))
+    set_plan(monkeypatch, FLCE_WINDOWS=windows, FLCE_VC_TILES=vc, FLCE_NC_TILES=nc, FLCE_GENERIC=generic)
     wl = custom(f"split_{dtype}_{generic}_{windows}_{vc}_{nc}", 700, 160, 1500, dtype, 21, ignore_frac=0.05)
     check_against_oracle(wl, I.make_inputs(wl))
 
@@ -112,11 +107,8 @@ def test_chunk_and_window_splits(monkeypatch, dtype, generic, windows, vc, nc):
 def test_split_k_contractions(monkeypatch, dtype, generic, sdh, sdw, vc, nc):
     """K of the dH / dW contractions cut into slices whose fp32 tiles are summed in slice order, with and
     without chunk accumulation on top."""
-    monkeypatch.setenv("FLCE_SPLITK_DH", str(sdh))
-    monkeypatch.setenv("FLCE_SPLITK_DW", str(sdw))
-    monkeypatch.setenv("FLCE_VC_TILES", str(vc))
-    monkeypatch.setenv("FLCE_NC_TILES", str(nc))
-    monkeypatch.setenv("FLCE_GENERIC", str(generic))
+    set_plan(monkeypatch, FLCE_SPLITK_DH=sdh, FLCE_SPLITK_DW=sdw, FLCE_VC_TILES=vc, FLCE_NC_TILES=nc,
+             FLCE_GENERIC=generic)
     wl = custom(f"splitk_{dtype}_{generic}_{sdh}_{sdw}_{vc}_{nc}", 1100, 288, 1800, dtype, 22, ignore_frac=0.08)
     check_against_oracle(wl, I.make_inputs(wl))
 
@@ -133,7 +125,7 @@ def test_generic_loop_matches_tuned_loop_closely(monkeypatch):
     wl = custom("both_loops", 520, 256, 2100, "bf16", 24, ignore_frac=0.1)
     x = I.make_inputs(wl)
     a = run_workload(wl, x)
-    monkeypatch.setenv("FLCE_GENERIC", "1")
+    set_plan(monkeypatch, FLCE_GENERIC=1)
     b = run_workload(wl, x)
     assert abs(a["loss"] - b["loss"]) <= 1e-6 * abs(a["loss"])
     assert nerr(a["dH"], b["dH"]) < 1e-2 and nerr(a["dW"], b["dW"]) < 1e-2
@@ -191,14 +183,23 @@ def test_out_of_range_target_is_flagged_and_dropped():
     assert f["out_of_range"] and got["n_valid"] == 298
 
 
-def test_results_are_bit_identical_between_runs():
+@pytest.mark.parametrize("env", [
+    {},
+    # several vocabulary and token chunks (fp32 running sums read and written back between launches) and K slices
+    # summed by the second kernel: the places where an order that depended on scheduling would show
+    {"FLCE_VC_TILES": "2", "FLCE_NC_TILES": "2", "FLCE_SPLITK_DH": "3", "FLCE_SPLITK_DW": "2", "FLCE_WINDOWS": "5"},
+    {"FLCE_VC_TILES": "3", "FLCE_NC_TILES": "1", "FLCE_SPLITK_DH": "2", "FLCE_SPLITK_DW": "1", "FLCE_GENERIC": "1"},
+], ids=["default_plan", "chunks_and_k_slices", "generic_loop_chunks"])
+def test_results_are_bit_identical_between_runs(monkeypatch, env):
+    set_plan(monkeypatch, **env)
     wl = custom("determinism", 1024, 256, 5000, "bf16", 61, targets="zipf", ignore_frac=0.05)
     x = I.make_inputs(wl)
     a = run_workload(wl, x)
     b = run_workload(wl, x)
+    c = run_workload(wl, x)
     for k in ("lse", "dH", "dW"):
-        assert np.array_equal(a[k], b[k]), k
-    assert a["loss"] == b["loss"]
+        assert np.array_equal(a[k], b[k]) and np.array_equal(a[k], c[k]), k
+    assert a["loss"] == b["loss"] == c["loss"]
 
 
 def test_gpt2_small_workload():
@@ -264,7 +265,7 @@ def test_vocabulary_slices_merge_to_the_whole(dtype, reduction):
     """The vocabulary cut into uneven slices (one exactly a tile, one a single row, ragged ends), each run through
     the partial calls and merged: per slice (m, a, z_target) against their definitions, the merged loss / lse and
     the assembled dW / summed dH against the two-stage oracle on the whole vocabulary."""
-    from paper_2511_17599_amd.runner import run_sliced
+    from sliced import run_sliced
     wl = custom(f"slices_{dtype}", 700, 160, 1500, dtype, 91, ignore_frac=0.1, reduction=reduction)
     x = I.make_inputs(wl)
     x["y"][5] = 1700                                         # one target outside the whole vocabulary
@@ -305,9 +306,7 @@ def test_per_row_losses_and_gradients(monkeypatch, dtype, eps, generic):
     """No reduction: one loss per row out, one upstream gradient per row in, with and without label smoothing,
     against the oracle's per-row functions (several chunks in the backward)."""
     from paper_2511_17599_amd.runner import session_for, to_host_f64, to_device
-    monkeypatch.setenv("FLCE_GENERIC", str(generic))
-    monkeypatch.setenv("FLCE_VC_TILES", "3")
-    monkeypatch.setenv("FLCE_NC_TILES", "2")
+    set_plan(monkeypatch, FLCE_GENERIC=generic, FLCE_VC_TILES=3, FLCE_NC_TILES=2)
     wl = custom(f"rows_{dtype}_{eps}_{generic}", 900, 160, 1700, dtype, 95, ignore_frac=0.1)
     x = I.make_inputs(wl)
     x["y"][11] = 5000                                        # outside the vocabulary: dropped and flagged
@@ -358,8 +357,7 @@ def _random_cases(n, seed):
 def test_seeded_random_shapes_and_plans(monkeypatch, case):
     """A fixed, seeded set of arbitrary shapes (ragged everywhere, d with and without the tuned loop), target
     mixes and launch plans (windows, chunk sizes, K splits)."""
-    for k, v in case["env"].items():
-        monkeypatch.setenv(k, v)
+    set_plan(monkeypatch, **case["env"])
     wl = case["wl"]
     print(f"[plan] {case['env']}", flush=True)
     check_against_oracle(wl, I.make_inputs(wl), grad_loss=case["grad_loss"])

@@ -35,7 +35,14 @@ def test_scalar_losses(reduction, eps):
     wl = I.Workload("api", 512, 96, 1000, "bf16", "uniform", ignore_frac=0.1, reduction=reduction, seed=301)
     x = I.make_inputs(wl)
     H, W, y = tensors(wl, x)
-    loss = linear_cross_entropy(H, W, y, reduction=reduction, label_smoothing=eps)
+    if eps == 0.0:
+        loss = linear_cross_entropy(H, W, y, reduction=reduction)
+    else:
+        # label smoothing comes per row; the caller reduces (here: the mean over counted rows, in torch)
+        with pytest.raises(ValueError):
+            linear_cross_entropy(H, W, y, reduction=reduction, label_smoothing=eps)
+        rows = linear_cross_entropy(H, W, y, reduction="none", label_smoothing=eps)
+        loss = rows.sum() / (y != wl.ignore_index).sum()
     (loss * 1.5).backward()
     Hd, Wd = I.to_f64(x["H"]), I.to_f64(x["W"])
     f = O.forward_per_row(Hd, Wd, x["y"], wl.ignore_index, eps)
