@@ -134,6 +134,33 @@ flce_status flce_backward(const void* H, const void* W, const int64_t* targets, 
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * flce_forward for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc).  Same computation and outputs as
+ * flce_forward; the scratch (per-window softmax partials, per-block sums, status header) lives in a device
+ * array inside the library, FLCE_STATIC_SCRATCH_BYTES large, that each GPU holds from the moment the library
+ * is loaded on it until the process ends.  The call allocates nothing and frees nothing: it looks up the
+ * array's address once per device, then only launches kernels on `hip_stream`.
+ *   Limit    : shapes whose forward scratch exceeds the array return FLCE_ERR_WORKSPACE and launch nothing.
+ *              The scratch is 12 * windows * ceil(N/256)*256 + 4 * ceil(V/1024) * d + 4 * N bytes + ~2 KiB
+ *              (windows = max(4, ceil(256 / ceil(N/256))) unless FLCE_WINDOWS says otherwise): N up to about
+ *              250 000 rows at d = 4096, V = 128256.  H is read in place (flce_forward's transposed copy of
+ *              H is what does not fit a fixed array), which costs a few per cent of speed at large d.
+ *   status_out, n_valid_out : device, one int32 / one int64, either may be NULL: the range flag (0 or
+ *              FLCE_ERR_TARGET_RANGE) and the number of counted rows of THIS call, written on the stream
+ *              (flce_last_device_status cannot be pointed at the internal array).
+ *   Sharing  : every call on a GPU uses that GPU's one array.  Nothing in it needs to start at zero (each
+ *              call overwrites what it reads), so calls in sequence on one stream, or ordered by events, are
+ *              fine whatever their shapes; calls that OVERLAP on one GPU (two streams, two threads) race on
+ *              it and give undefined results.
+ */
+#define FLCE_STATIC_SCRATCH_BYTES (16u << 20)
+flce_status flce_forward_static(const void* H, const void* W, const int64_t* targets,
+                                int64_t N, int64_t d, int64_t V, int64_t ignore_index,
+                                flce_reduction reduction, flce_dtype dt,
+                                float* loss_out, float* lse_out,
+                                int32_t* status_out, int64_t* n_valid_out, void* hip_stream);
+
+/*
  * Forward with partial gradient accumulation (Alg. 3): the loss and lse of flce_forward
  * plus the gradients not yet scaled by the upstream gradient,
  *   dH_partial[i] = sum_v (P_iv - 1[v = y_i]) W_v,   dW_partial[v] = sum_i (P_iv - 1[v = y_i]) H_i,

@@ -17,8 +17,9 @@ FLCE_OK, FLCE_ERR_BAD_ARG, FLCE_ERR_BAD_SHAPE, FLCE_ERR_WORKSPACE = 0, 1, 2, 3
 FLCE_ERR_TARGET_RANGE, FLCE_ERR_UNSUPPORTED, FLCE_ERR_HIP = 4, 5, 6
 FLCE_DTYPE_BF16, FLCE_DTYPE_F32 = 0, 1
 FLCE_REDUCE_MEAN, FLCE_REDUCE_SUM = 0, 1
+FLCE_STATIC_SCRATCH_BYTES = 16 << 20
 
-EXPORTS = ("flce_version", "flce_tuning_reload", "flce_status_string", "flce_workspace_bytes", "flce_forward", "flce_backward",
+EXPORTS = ("flce_version", "flce_tuning_reload", "flce_status_string", "flce_workspace_bytes", "flce_forward", "flce_backward", "flce_forward_static",
            "flce_forward_with_grads", "flce_scale", "flce_forward_rows", "flce_backward_rows", "flce_forward_partial", "flce_merge_workspace_bytes",
            "flce_merge_partials", "flce_backward_partial", "flce_last_device_status", "flce_profile_enable",
            "flce_profile_collect")
@@ -46,6 +47,10 @@ def lib():
         L.flce_forward.restype = c.c_int
         L.flce_forward.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_int64,
                                    c.c_int, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+        L.flce_forward_static.restype = c.c_int
+        L.flce_forward_static.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
+                                          c.c_int64, c.c_int, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p,
+                                          c.c_void_p, c.c_void_p]
         L.flce_backward.restype = c.c_int
         L.flce_backward.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64,
                                     c.c_int64, c.c_int, c.c_int, c.c_float, c.c_void_p, c.c_void_p, c.c_void_p,
@@ -125,6 +130,13 @@ def flce_forward(H, W, targets, N, d, V, ignore_index, reduction, dt, loss_out, 
                  hip_stream=None):
     return lib().flce_forward(_ptr(H), _ptr(W), _ptr(targets), N, d, V, ignore_index, reduction, dt, _ptr(loss_out),
                               _ptr(lse_out), _ptr(workspace), workspace_bytes, _stream(hip_stream))
+
+
+def flce_forward_static(H, W, targets, N, d, V, ignore_index, reduction, dt, loss_out, lse_out, status_out=None,
+                        n_valid_out=None, hip_stream=None):
+    return lib().flce_forward_static(_ptr(H), _ptr(W), _ptr(targets), N, d, V, ignore_index, reduction, dt,
+                                     _ptr(loss_out), _ptr(lse_out), _ptr(status_out), _ptr(n_valid_out),
+                                     _stream(hip_stream))
 
 
 def flce_backward(H, W, targets, lse, N, d, V, ignore_index, reduction, dt, grad_loss, dH_out, dW_out, workspace,

@@ -12,6 +12,11 @@
 
 #include "kernels.h"
 
+// Workspace of flce_forward_static, the forward for callers that cannot allocate: a file-scope device array.
+// Every GPU the library is loaded on holds its own copy, at its own address, until the process ends.  In host
+// code this name is only a handle for hipGetSymbolAddress; kernels are given the address that call returns.
+static __device__ __align__(256) unsigned char scratch[FLCE_STATIC_SCRATCH_BYTES];
+
 namespace flce {
 namespace {
 
@@ -474,6 +479,39 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+constexpr size_t STATIC_SCRATCH_BYTES = FLCE_STATIC_SCRATCH_BYTES;
+
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up once per device), or nullptr.
+hipError_t static_scratch(void** out) {
+  *out = nullptr;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(::scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+// Hands the status header of a finished forward to the caller's own device words (either may be null).
+__global__ void export_header_kernel(const Header* __restrict__ hdr, int32_t* __restrict__ status_out,
+                                     int64_t* __restrict__ n_valid_out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    if (status_out) *status_out = hdr->status;
+    if (n_valid_out) *n_valid_out = hdr->n_valid;
+  }
+}
+
 }  // namespace
 }  // namespace flce
 
@@ -584,6 +622,31 @@ flce_status flce_backward(const void* H, const void* W, const int64_t* targets, 
                           void* hip_stream) {
   return backward_impl(H, W, targets, lse, N, d, V, ignore_index, reduction, dt, grad_loss, dH_out, dW_out,
                        workspace, workspace_bytes, hip_stream, flce::Slice{V, 0});
+}
+
+flce_status flce_forward_static(const void* H, const void* W, const int64_t* targets, int64_t N, int64_t d, int64_t V,
+                                int64_t ignore_index, flce_reduction reduction, flce_dtype dt, float* loss_out,
+                                float* lse_out, int32_t* status_out, int64_t* n_valid_out, void* hip_stream) {
+  // The plan without the transposed copy of H (its size grows with N*d): what is left of the forward
+  // workspace is the per-window partials and per-block sums, O(N) words.
+  if (!H || !W || !targets || !loss_out || !lse_out) return FLCE_ERR_BAD_ARG;
+  if (reduction != FLCE_REDUCE_MEAN && reduction != FLCE_REDUCE_SUM) return FLCE_ERR_BAD_ARG;
+  if (dt != FLCE_DTYPE_BF16 && dt != FLCE_DTYPE_F32) return FLCE_ERR_BAD_ARG;
+  flce::Plan p;
+  if (!flce::make_plan(N, d, V, dt, p, /*allow_h_copy=*/false)) return FLCE_ERR_BAD_SHAPE;
+  if ((size_t)p.fwd_bytes > flce::STATIC_SCRATCH_BYTES) return FLCE_ERR_WORKSPACE;
+  void* ws = nullptr;
+  if (flce::static_scratch(&ws) != hipSuccess) return FLCE_ERR_HIP;
+  const flce_status st = forward_impl(H, W, targets, N, d, V, ignore_index, reduction, dt, loss_out, lse_out, ws,
+                                      flce::STATIC_SCRATCH_BYTES, hip_stream, flce::Slice{V, 0}, nullptr, nullptr,
+                                      nullptr, flce::PerRow{nullptr, nullptr, 0.f}, /*allow_h_copy=*/false);
+  if (st != FLCE_OK) return st;
+  if (status_out || n_valid_out) {
+    flce::export_header_kernel<<<1, 64, 0, static_cast<hipStream_t>(hip_stream)>>>(
+        static_cast<const flce::Header*>(ws), status_out, n_valid_out);
+    if (hipGetLastError() != hipSuccess) return FLCE_ERR_HIP;
+  }
+  return FLCE_OK;
 }
 
 flce_status flce_forward_rows(const void* H, const void* W, const int64_t* targets, int64_t N, int64_t d, int64_t V,
