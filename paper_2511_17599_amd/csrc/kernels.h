@@ -44,6 +44,8 @@ struct GenericLoop {      // any dtype, any K that is a multiple of 16 bytes; 8 
   static __device__ __forceinline__ int slot() {
     return ((threadIdx.x >> 6) >> 2) * 2 + ((threadIdx.x & 63) >> 5);
   }
+  // element r of an accumulator block, for the code that post-processes a finished tile
+  static __device__ __forceinline__ float acc_get(const f32x16& blk, int r) { return blk[r]; }
   static __device__ __forceinline__ void run(const void* A, int64_t lda_bytes, int a_row0, int a_rows, const void* B,
                                              int64_t ldb_bytes, int b_row0, int b_rows, int k_bytes, char* lds,
                                              f32x16 (&acc)[WM][WN]) {
@@ -59,6 +61,14 @@ struct FastLoop {         // bf16, K a multiple of 32 elements; 4 wavefronts 2 x
   static __device__ __forceinline__ int tile_m(int i, int r) { return fast::tile_m(i, r); }
   static __device__ __forceinline__ int tile_n(int j) { return fast::tile_n(j); }
   static __device__ __forceinline__ int slot() { return fast::slot_of_lane(); }
+  // The 256 accumulators of a wavefront live in the accumulation registers.  Post-processing reads them one
+  // block at a time where it uses them; left to itself the compiler copies most of a tile into vector
+  // registers in one sweep at the end of the main loop, which overflows the register file into scratch memory.
+  static __device__ __forceinline__ float acc_get(const f32x16& blk, int r) {   // r: a constant after unrolling
+    float v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(blk[r]));
+    return v;
+  }
   static __device__ __forceinline__ void run(const void* A, int64_t lda_bytes, int a_row0, int a_rows, const void* B,
                                              int64_t ldb_bytes, int b_row0, int b_rows, int k_bytes, char* lds,
                                              f32x16 (&acc)[WM][WN]) {
@@ -202,11 +212,15 @@ __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
         if (blk0 >= V) continue;
         float z[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) z[r] = acc[i][j][r];
+        for (int r = 0; r < 16; ++r) z[r] = L::acc_get(acc[i][j], r);
+        // Row of register r inside its 32-row block: 8 * (r / 4) + (r % 4), a constant, plus 4 for the upper
+        // half of the lanes (the 32x32 MFMA's accumulator layout); comparisons are written against the constant.
+        const int half4 = L::tile_m(i, 0) & 4;
         if (blk0 + 32 > V) {
+          const int live = V - blk0 - half4;                // rows of this block below the vocabulary's end, per lane half
 #pragma unroll
           for (int r = 0; r < 16; ++r)
-            if (v0 + L::tile_m(i, r) >= V) z[r] = NEG_INF;
+            if ((r >> 2) * 8 + (r & 3) >= live) z[r] = NEG_INF;
         }
         float bmax = z[0];
 #pragma unroll
@@ -223,9 +237,10 @@ __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
         const int rel = tgt[j] - blk0;                    // target row inside this block, if any
         const bool mine = (unsigned)rel < 32u && tgt[j] >= 0;
         if (__ballot(mine) != 0ull) {
+          const int relh = rel - half4;
 #pragma unroll
           for (int r = 0; r < 16; ++r)
-            if (mine && (L::tile_m(i, r) & 31) == rel) zt[j] = z[r];
+            if (mine && (r >> 2) * 8 + (r & 3) == relh) zt[j] = z[r];
         }
         // one block at a time in VGPRs
         __builtin_amdgcn_sched_barrier(0);
@@ -581,13 +596,18 @@ __device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bi
     const int nl = p * TILE + L::tile_n(j);       // row inside the staging tile
     const int n = n0 + L::tile_n(j);
     const int tgt = tgt_c[n];
-    const bool counted = tgt >= 0;
-    const float l = lse_c[n];
-    const float ll = -l * LOG2E;                      // exp(z - lse) = 2^(z * log2e - lse * log2e)
+    // exp(z - lse) = 2^(z * log2e - lse * log2e); a padding row (tgt < 0) gets lse = +inf here, so its p is
+    // exactly 0, and no column equals its target: its row of G is 0 without a mask
+    const float ll = tgt >= 0 ? -lse_c[n] * LOG2E : NEG_INF;
     float gam = 1.f;
-    if constexpr (PER_ROW) gam = a.gam_c[n];
+    if constexpr (PER_ROW) gam = tgt >= 0 ? a.gam_c[n] : 0.f;
+    const float unif = tgt >= 0 ? a.uniform_part : 0.f;
 #pragma unroll
-    for (int i = 0; i < L::WM; ++i)
+    for (int i = 0; i < L::WM; ++i) {
+      // All 32 vocabulary positions of a block belong to one wavefront: "behind the vocabulary's end" and
+      // "straddles the end" are wave-uniform tests, and only a straddling block masks single elements.
+      const int blk0 = v0 + __builtin_amdgcn_readfirstlane(L::tile_m(i, 0) & ~31);
+      const bool whole = blk0 + 32 <= V;
 #pragma unroll
       for (int rq = 0; rq < 4; ++rq) {
         const int mloc = L::tile_m(i, rq * 4);    // first of 4 consecutive vocabulary positions
@@ -595,10 +615,15 @@ __device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bi
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int v = v0 + mloc + e;
-          float pz = fast_exp2(fmaf(acc[i][j][rq * 4 + e], LOG2E, ll));
-          if constexpr (PER_ROW) pz = gam * (pz - ((v == tgt) ? a.onehot_weight : 0.f) - a.uniform_part);
+          float pz = fast_exp2(fmaf(L::acc_get(acc[i][j], rq * 4 + e), LOG2E, ll));
+          if constexpr (PER_ROW) pz = gam * (pz - ((v == tgt) ? a.onehot_weight : 0.f) - unif);
           else pz -= (v == tgt) ? 1.f : 0.f;
-          g[e] = (counted && v < V) ? pz : 0.f;
+          g[e] = pz;
+        }
+        if (!whole) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (v0 + mloc + e >= V) g[e] = 0.f;
         }
         const int vl = q * TILE + mloc;
         Pack4<T>::store(G + (int64_t)nl * ldG + vl, g[0], g[1], g[2], g[3]);
@@ -606,8 +631,9 @@ __device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bi
 #pragma unroll
           for (int e = 0; e < 4; ++e) GT[(int64_t)(vl + e) * ldGT + nl] = Pack4<T>::one(g[e]);
         }
-        if (rq == 3) __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
       }
+      __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
+    }
   }
 }
 
@@ -718,7 +744,8 @@ __device__ __forceinline__ void contract_tile(const ContractArgs<T>& a, int bid,
       for (int rq = 0; rq < 4; ++rq) {
         const int m = q * TILE + L::tile_m(i, rq * 4);
         if (m >= d) continue;
-        f32x4 v = {acc[i][j][rq * 4], acc[i][j][rq * 4 + 1], acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]};
+        f32x4 v = {L::acc_get(acc[i][j], rq * 4), L::acc_get(acc[i][j], rq * 4 + 1), L::acc_get(acc[i][j], rq * 4 + 2),
+                   L::acc_get(acc[i][j], rq * 4 + 3)};
         float* ap = accbuf + (int64_t)(n - acc_row0) * d + m;
         if (flags & READ_ACC) v += *reinterpret_cast<const f32x4*>(ap);
         if (flags & WRITE_ACC) *reinterpret_cast<f32x4*>(ap) = v;
