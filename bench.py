@@ -117,6 +117,48 @@ def sweep_paper_grid(steps, warmup):
         del W
 
 
+def probe_main_loop(steps, warmup):
+    """What the pieces of the tuned main loop sustain on their own (flce_probe): one JSON line per mode and K."""
+    import torch
+    from paper_2511_17599_amd import binding as B
+
+    torch.cuda.set_device(0)
+    props = torch.cuda.get_device_properties(0)
+    g = torch.Generator(device="cuda").manual_seed(3001)
+    wgs = 256
+    for k, a_rows, b_rows, tiles in ((4096, 32768, 8192, 32), (768, 50176, 4096, 96)):
+        A = (torch.randn(a_rows, k, device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+        Bm = torch.randn(b_rows, k, device="cuda", generator=g).to(torch.bfloat16)
+        BT = Bm.t().contiguous()
+        sink = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+        st = torch.cuda.current_stream()
+        for mode, name in enumerate(B.PROBE_MODES):
+            ms = []
+            for it in range(warmup + steps):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(st)
+                rc = B.flce_probe(mode, A, Bm, BT, a_rows, b_rows, k, wgs, tiles, sink, st)
+                e1.record(st)
+                assert rc == B.FLCE_OK, B.flce_status_string(rc)
+                e1.synchronize()
+                if it >= warmup:
+                    ms.append(e0.elapsed_time(e1))
+            ms.sort()
+            med = ms[len(ms) // 2]
+            flops = 2.0 * 256 * 256 * k * tiles * wgs
+            lds_bytes = 2.0 * 256 * k * 2 * tiles * wgs                # operand bytes brought into LDS
+            line = {"probe": name, "k_elems": k, "workgroups": wgs, "tiles_per_workgroup": tiles,
+                    "ms_median": med, "ms_min": ms[0], "device": props.name, "compute_units": props.multi_processor_count}
+            if name.startswith("data"):
+                line["global_to_lds_TBps"] = lds_bytes / (med * 1e-3) / 1e12
+                line["mfma_time_equivalent_tflops"] = flops / (med * 1e-3) / 1e12
+            else:
+                line["tflops"] = flops / (med * 1e-3) / 1e12
+                line["frac_of_nominal_peak"] = line["tflops"] / BF16_MFMA_PEAK_TFLOPS
+            print(json.dumps(line), flush=True)
+        del A, Bm, BT
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -134,6 +176,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time its replays (launch-bound shapes); implies "
                          "--no-profile")
+    ap.add_argument("--probe", action="store_true",
+                    help="instead of the benchmark line: the rates of the matrix pipe alone, of the bare tuned main "
+                         "loop and of its data path alone (flce_probe)")
     ap.add_argument("--sweep", choices=["paper_table2"], default=None,
                     help="instead of the benchmark line: latency and memory over the paper's evaluation grid")
     args = ap.parse_args()
@@ -143,6 +188,9 @@ def main():
 
     if args.sweep:
         sweep_paper_grid(args.steps, args.warmup)
+        return
+    if args.probe:
+        probe_main_loop(args.steps, args.warmup)
         return
 
     import numpy as np

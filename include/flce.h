@@ -295,6 +295,26 @@ enum {
 flce_status flce_profile_enable(int on);
 flce_status flce_profile_collect(double* ms_by_class, int64_t* launches_by_class);
 
+/*
+ * Second measurement aid (not part of the computation): runs a piece of the tuned bf16 main loop on its own, so
+ * that a kernel's rate can be compared with what the matrix pipe and the bare loop sustain on this chip, not
+ * only with the nominal peak.  `workgroups` workgroups of 4 wavefronts each walk `tiles_per_workgroup` tiles
+ * of 256 x 256 outputs over K = k_elems.
+ *   mode 0 : the 32x32x16 bf16 MFMA back to back from registers (no memory traffic in the loop)
+ *   mode 1 : the complete main loop, A K-contiguous and B read across memory rows (forward / recompute layout)
+ *   mode 2 : the complete main loop, both operands K-contiguous
+ *   mode 3, 4 : modes 1, 2 with the matrix instructions left out (global -> LDS requests, LDS reads, waits and
+ *            barriers only): the data path alone
+ *   A  : device, bf16 [a_rows][k_elems];  B : device, bf16 [b_rows][k_elems];  BT : device, bf16 [k_elems][b_rows]
+ *        (a_rows, b_rows multiples of 256, k_elems a multiple of 32); contents are the caller's choice of data.
+ *   sink : device, workgroups * 256 floats, written once per thread.
+ * Every mode executes 2 * 256 * 256 * k_elems * tiles_per_workgroup * workgroups nominal flops (modes 3, 4 move
+ * the bytes of as many tiles).  Enqueues one kernel on `hip_stream`; the caller times it.
+ */
+flce_status flce_probe(int mode, const void* A, const void* B, const void* BT,
+                       int64_t a_rows, int64_t b_rows, int64_t k_elems,
+                       int workgroups, int tiles_per_workgroup, float* sink, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

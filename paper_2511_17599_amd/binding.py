@@ -22,7 +22,7 @@ FLCE_STATIC_SCRATCH_BYTES = 16 << 20
 EXPORTS = ("flce_version", "flce_tuning_reload", "flce_status_string", "flce_workspace_bytes", "flce_forward", "flce_backward", "flce_forward_static",
            "flce_forward_with_grads", "flce_scale", "flce_forward_rows", "flce_backward_rows", "flce_forward_partial", "flce_merge_workspace_bytes",
            "flce_merge_partials", "flce_backward_partial", "flce_last_device_status", "flce_profile_enable",
-           "flce_profile_collect")
+           "flce_profile_collect", "flce_probe")
 PROF_CLASSES = ("fwd_tiles", "fwd_epilogue", "bwd_prep", "recompute", "contract_dW", "contract_dH", "scale")
 
 _lib = None
@@ -90,6 +90,9 @@ def lib():
         L.flce_profile_enable.argtypes = [c.c_int]
         L.flce_profile_collect.restype = c.c_int
         L.flce_profile_collect.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64)]
+        L.flce_probe.restype = c.c_int
+        L.flce_probe.argtypes = [c.c_int, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_int,
+                                 c.c_int, c.c_void_p, c.c_void_p]
         _lib = L
     return _lib
 
@@ -215,3 +218,11 @@ def flce_profile_collect():
     cnt = (ctypes.c_int64 * n)()
     st = lib().flce_profile_collect(ms, cnt)
     return st, dict(zip(PROF_CLASSES, list(ms))), dict(zip(PROF_CLASSES, list(cnt)))
+
+
+PROBE_MODES = ("mfma_only", "loop_kc_kr", "loop_kc_kc", "data_kc_kr", "data_kc_kc")
+
+
+def flce_probe(mode, A, B, BT, a_rows, b_rows, k_elems, workgroups, tiles_per_workgroup, sink, hip_stream=None):
+    return lib().flce_probe(int(mode), _ptr(A), _ptr(B), _ptr(BT), a_rows, b_rows, k_elems, workgroups,
+                            tiles_per_workgroup, _ptr(sink), _stream(hip_stream))

@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "kernels.h"
+#include "probe.h"
 
 // Workspace of flce_forward_static, the forward for callers that cannot allocate: a file-scope device array.
 // Every GPU the library is loaded on holds its own copy, at its own address, until the process ends.  In host
@@ -774,6 +775,33 @@ flce_status flce_last_device_status(const void* workspace, void* hip_stream, int
   if (hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) return FLCE_ERR_HIP;
   if (n_valid_out) *n_valid_out = h.n_valid;
   return h.status == 0 ? FLCE_OK : FLCE_ERR_TARGET_RANGE;
+}
+
+flce_status flce_probe(int mode, const void* A, const void* B, const void* BT, int64_t a_rows, int64_t b_rows,
+                       int64_t k_elems, int workgroups, int tiles_per_workgroup, float* sink, void* hip_stream) {
+  if (!A || !B || !BT || !sink) return FLCE_ERR_BAD_ARG;
+  if (a_rows <= 0 || b_rows <= 0 || (a_rows % flce::TILE) || (b_rows % flce::TILE) || k_elems < 32 || (k_elems % 32) ||
+      workgroups <= 0 || tiles_per_workgroup <= 0)
+    return FLCE_ERR_BAD_SHAPE;
+  if (!flce::window_ok(257, k_elems * 2) || !flce::window_ok(k_elems, b_rows * 2)) return FLCE_ERR_BAD_SHAPE;
+  if (!flce::aligned16(A) || !flce::aligned16(B) || !flce::aligned16(BT)) return FLCE_ERR_BAD_ARG;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const flce::ProbeArgs pa{static_cast<const flce::bf16_t*>(A), static_cast<const flce::bf16_t*>(B),
+                           static_cast<const flce::bf16_t*>(BT), (int)a_rows, (int)b_rows, (int)k_elems,
+                           tiles_per_workgroup, sink};
+  auto launch = [&](auto kernel) -> flce_status {
+    if (flce::allow_big_lds(kernel, flce::fast::LDS_BYTES) != hipSuccess) return FLCE_ERR_HIP;
+    kernel<<<workgroups, flce::fast::THREADS, flce::fast::LDS_BYTES, st>>>(pa);
+    return hipGetLastError() == hipSuccess ? FLCE_OK : FLCE_ERR_HIP;
+  };
+  switch (mode) {
+    case flce::PROBE_MFMA: return launch(flce::probe_kernel<flce::PROBE_MFMA>);
+    case flce::PROBE_LOOP_KR: return launch(flce::probe_kernel<flce::PROBE_LOOP_KR>);
+    case flce::PROBE_LOOP_KC: return launch(flce::probe_kernel<flce::PROBE_LOOP_KC>);
+    case flce::PROBE_DATA_KR: return launch(flce::probe_kernel<flce::PROBE_DATA_KR>);
+    case flce::PROBE_DATA_KC: return launch(flce::probe_kernel<flce::PROBE_DATA_KC>);
+  }
+  return FLCE_ERR_BAD_ARG;
 }
 
 flce_status flce_profile_enable(int on) {

@@ -46,6 +46,20 @@ struct GenericLoop {      // any dtype, any K that is a multiple of 16 bytes; 8 
   }
   // element r of an accumulator block, for the code that post-processes a finished tile
   static __device__ __forceinline__ float acc_get(const f32x16& blk, int r) { return blk[r]; }
+  // A sequence of tiles A[a_row0 ..][:] x B[b_row0 ..][:] over K = k_elems; start() names the next tile, run() computes
+  // it.  This loop has nothing to request ahead: start() only records the operands.
+  template <bool BT>
+  struct Stream {
+    TileSrc As, Bs;
+    int k_bytes;
+    __device__ __forceinline__ void start(const T* A, int64_t lda_bytes, int a_row0, int a_rows, const T* B, const T*,
+                                          int64_t ldb_bytes, int64_t, int b_row0, int b_rows, int k_elems, char*) {
+      As = TileSrc{reinterpret_cast<const char*>(A), lda_bytes, a_row0, a_rows};
+      Bs = TileSrc{reinterpret_cast<const char*>(B), ldb_bytes, b_row0, b_rows};
+      k_bytes = k_elems * (int)sizeof(T);
+    }
+    __device__ __forceinline__ void run(char* lds, f32x16 (&acc)[WM][WN]) { tile_mainloop<T>(As, Bs, k_bytes, lds, acc); }
+  };
   static __device__ __forceinline__ void run(const void* A, int64_t lda_bytes, int a_row0, int a_rows, const void* B,
                                              int64_t ldb_bytes, int b_row0, int b_rows, int k_bytes, char* lds,
                                              f32x16 (&acc)[WM][WN]) {
@@ -64,6 +78,25 @@ struct FastLoop {         // bf16, K a multiple of 32 elements; 4 wavefronts 2 x
   // The 256 accumulators of a wavefront live in the accumulation registers.  Post-processing reads them one
   // block at a time where it uses them; left to itself the compiler copies most of a tile into vector
   // registers in one sweep at the end of the main loop, which overflows the register file into scratch memory.
+  // A sequence of tiles with the same B operand: start() requests the first K stages of a tile (all LDS stages must
+  // be free: every wavefront is past the previous run()), run() computes it.  BT: B is given transposed, BT[k][n].
+  template <bool BT>
+  struct Stream {
+    fast::Pipe<fast::KC, BT ? fast::KR : fast::KC> pipe;
+    __device__ __forceinline__ void start(const bf16_t* A, int64_t lda_bytes, int a_row0, int a_rows, const bf16_t* B,
+                                          const bf16_t* Bt, int64_t ldb_bytes, int64_t ldbt_bytes, int b_row0,
+                                          int b_rows, int k_elems, char* lds) {
+      const fast::Operand As{reinterpret_cast<const char*>(A), lda_bytes, a_row0, a_rows, 0};
+      if constexpr (BT) {
+        const fast::Operand Bs{reinterpret_cast<const char*>(Bt) + (int64_t)b_row0 * 2, ldbt_bytes, 0, k_elems, TILE * 2};
+        pipe.start(As, Bs, k_elems, lds);
+      } else {
+        const fast::Operand Bs{reinterpret_cast<const char*>(B), ldb_bytes, b_row0, b_rows, 0};
+        pipe.start(As, Bs, k_elems, lds);
+      }
+    }
+    __device__ __forceinline__ void run(char* lds, f32x16 (&acc)[WM][WN]) { pipe.run(lds, acc); }
+  };
   static __device__ __forceinline__ float acc_get(const f32x16& blk, int r) {   // r: a constant after unrolling
     float v;
     asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(blk[r]));
@@ -195,10 +228,14 @@ __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
   }
 
   f32x16 acc[L::WM][L::WN];
+  // The tuned loop's first K stages of tile t+1 are requested before the softmax update of tile t (which touches
+  // no memory), so the update hides their latency: it matters when the K loop is short (small d).
+  typename L::template Stream<HKR> stream;
+  if (vt_begin < vt_end) stream.start(W, ld_bytes, vt_begin * TILE, V, H, HT, ld_bytes, (int64_t)n_rb * TILE * sizeof(T), n0, N, d, lds);
   for (int vt = vt_begin; vt < vt_end; ++vt) {
     const int v0 = vt * TILE;
-    if constexpr (HKR) L::run_bt(W, ld_bytes, v0, V, HT, (int64_t)n_rb * TILE * sizeof(T), n0, d, lds, acc);
-    else L::run(W, ld_bytes, v0, V, H, ld_bytes, n0, N, (int)ld_bytes, lds, acc);
+    stream.run(lds, acc);
+    if (vt + 1 < vt_end) stream.start(W, ld_bytes, v0 + TILE, V, H, HT, ld_bytes, (int64_t)n_rb * TILE * sizeof(T), n0, N, d, lds);
 
     // Online update of (m, a) and the target gather, one 32 x 32 accumulator block at a time
     // (16 logits of one token per lane).  All 32 rows of a block belong to one wavefront, so

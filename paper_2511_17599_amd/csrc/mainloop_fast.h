@@ -30,6 +30,8 @@
 // Requires the K extent to be a multiple of 32 elements and offsets inside one tile's
 // address window within 2^32 bytes (unsigned 32-bit buffer offsets); the generic loop in tile_mma.h covers everything else.
 #pragma once
+#include <type_traits>
+
 #include "tile_mma.h"
 
 namespace flce {
@@ -202,7 +204,10 @@ __device__ __forceinline__ void read_frag(bf16x8 (&f)[4], const FragAddr<LAYOUT>
 //   run(lds, acc):             acc = A_tile . B_tile^T over k_elems of K (a multiple of 32).  On
 //                              return all wavefronts have passed a barrier after their last LDS
 //                              read, so the caller may reuse `lds` or call start() again.
-template <int LA, int LB>
+//
+// WITH_MFMA = false leaves the matrix instructions out (everything else, i.e. the global -> LDS requests, the LDS
+// fragment reads, the waits and barriers, stays): only the measurement probe uses it, to time the data path alone.
+template <int LA, int LB, bool WITH_MFMA = true>
 struct Pipe {
   Loader<LA> la;
   Loader<LB> lb;
@@ -229,13 +234,17 @@ struct Pipe {
   }
 
   __device__ __forceinline__ void run(char* lds, f32x16 (&acc)[WM][WN]) {
-#pragma unroll
-    for (int i = 0; i < WM; ++i)
-#pragma unroll
-      for (int j = 0; j < WN; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     constexpr int RA = FragAddr<LA>::READS, RB = FragAddr<LB>::READS, RT = RA + RB;
+    if (KT <= 0) {          // an empty K extent (no counted row, or a K slice past the end): the tile is zero
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      __builtin_amdgcn_s_barrier();
+      return;
+    }
 
     // tile 0 has landed once at most tiles 1 and 2 are in flight
     if (KT > 2) wait_vm_and_lds<2 * LOADS_PER_TILE>();
@@ -251,12 +260,25 @@ struct Pipe {
     // One half of a K step: the 16 MFMAs of fragment set FM; between them the LDS reads that
     // fill fragment set FR (stage `st`, MFMA K step ks) and, if load_kt >= 0, the 4 global
     // requests of operand `which` (0 = A, 1 = B) of K tile load_kt into stage `lst`.
-    auto half_step = [&](const Frags& FM, Frags& FR, const char* st, int ks, int which, int load_kt, char* lst) {
+    // `first`: the very first half step of a tile starts every accumulator block from zero (the
+    // matrix instruction takes the constant as its addend: no pass over the 256 registers to clear them).
+    auto half_step = [&](auto first, const Frags& FM, Frags& FR, const char* st, int ks, int which, int load_kt,
+                         char* lst) {
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int s = 0; s < 16; ++s) {
         const int mi = s >> 2, mj = s & 3;
-        acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FM.a[mi], FM.b[mj], acc[mi][mj], 0, 0, 0);
+        if constexpr (WITH_MFMA) {
+          if constexpr (decltype(first)::value) {
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FM.a[mi], FM.b[mj], zero, 0, 0, 0);
+          } else {
+            acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FM.a[mi], FM.b[mj], acc[mi][mj], 0, 0, 0);
+          }
+        } else {
+          // keep the fragment reads alive without arithmetic on them
+          asm volatile("" ::"v"(FM.a[mi]), "v"(FM.b[mj]));
+        }
         // reads t with t * 16 / RT == s: spread evenly over the 16 slots
 #pragma unroll
         for (int t = 0; t < RT; ++t)
@@ -271,31 +293,40 @@ struct Pipe {
         __builtin_amdgcn_sched_barrier(0);
       }
     };
+    constexpr std::true_type FIRST{};
+    constexpr std::false_type LATER{};
 
     // Steady state: K step kt computes tile kt and requests tile kt+3 into the stage that
     // was freed by the barrier of step kt-1.
-    int kt = 0;
-    for (; kt + NS - 1 < KT; ++kt) {
+    auto steady_step = [&](auto first, int kt) {
       const char* cur = lds + (kt & (NS - 1)) * STAGE;
       const char* nxt = lds + ((kt + 1) & (NS - 1)) * STAGE;
       char* lst = lds + ((kt + NS - 1) & (NS - 1)) * STAGE;
-      half_step(f0, f1, cur, 1, 0, kt + NS - 1, lst);
+      half_step(first, f0, f1, cur, 1, 0, kt + NS - 1, lst);
       // tile kt+1 has landed once only tile kt+2 and the first half of tile kt+3 are in flight;
       // lgkmcnt(0): this wavefront holds all its fragments of tile kt
       wait_vm_and_lds<LOADS_PER_TILE + LOADS_PER_TILE / 2>();
       __builtin_amdgcn_s_barrier();
-      half_step(f1, f0, nxt, 0, 1, kt + NS - 1, lst);
-    }
+      half_step(LATER, f1, f0, nxt, 0, 1, kt + NS - 1, lst);
+    };
     // Drain: the last (up to NS-1) tiles, nothing left to request.
-    for (; kt < KT; ++kt) {
+    auto drain_step = [&](auto first, int kt) {
       const char* cur = lds + (kt & (NS - 1)) * STAGE;
       const char* nxt = lds + ((kt + 1) & (NS - 1)) * STAGE;   // past the last tile: stale data, never used
-      half_step(f0, f1, cur, 1, 0, -1, nullptr);
+      half_step(first, f0, f1, cur, 1, 0, -1, nullptr);
       if (kt + 2 < KT) wait_vm_and_lds<LOADS_PER_TILE>();
       else wait_vm_and_lds<0>();
       __builtin_amdgcn_s_barrier();
-      half_step(f1, f0, nxt, 0, 1, -1, nullptr);
+      half_step(LATER, f1, f0, nxt, 0, 1, -1, nullptr);
+    };
+    int kt = 1;
+    if (NS - 1 < KT) {
+      steady_step(FIRST, 0);
+      for (; kt + NS - 1 < KT; ++kt) steady_step(LATER, kt);
+    } else {
+      drain_step(FIRST, 0);
     }
+    for (; kt < KT; ++kt) drain_step(LATER, kt);
     wait_vm_and_lds<0>();
     __builtin_amdgcn_s_barrier();
   }

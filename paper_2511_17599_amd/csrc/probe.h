@@ -1,0 +1,101 @@
+// Measurement probe (not part of the computation): what the pieces of the tuned main loop sustain on their own on
+// this chip, so that a kernel's rate can be read against the rate of the matrix pipe alone and of the bare loop
+// rather than against the nominal peak only.  One workgroup per CU-sized slot, 4 wavefronts, as in the real kernels.
+//   PROBE_MFMA     : the 32x32x16 bf16 MFMA issued back to back from registers (fragments loaded once): the rate
+//                    the matrix pipe sustains under the chip's power limit with this data.
+//   PROBE_LOOP_KR  : the complete main loop of the forward / recompute (A K-contiguous, B read across memory rows),
+//                    tile after tile with no post-processing of the accumulators.
+//   PROBE_LOOP_KC  : the same with both operands K-contiguous.
+//   PROBE_DATA_KR / PROBE_DATA_KC : those loops with the matrix instructions left out (global -> LDS requests, LDS
+//                    fragment reads, waits, barriers only): the data path alone.
+#pragma once
+#include "mainloop_fast.h"
+
+namespace flce {
+
+enum : int { PROBE_MFMA = 0, PROBE_LOOP_KR = 1, PROBE_LOOP_KC = 2, PROBE_DATA_KR = 3, PROBE_DATA_KC = 4 };
+
+struct ProbeArgs {
+  const bf16_t* A;      // [a_rows][k_elems], K-contiguous (plays W)
+  const bf16_t* B;      // [b_rows][k_elems], K-contiguous (plays H)
+  const bf16_t* BT;     // [k_elems][b_rows] (plays H transposed)
+  int a_rows, b_rows, k_elems;
+  int tiles_per_wg;     // tiles each workgroup walks along A (wrapping around a_rows)
+  float* sink;          // [gridDim.x * 256] one float per thread, so that nothing is optimised away
+};
+
+template <int MODE>
+__global__ __launch_bounds__(fast::THREADS) void probe_kernel(ProbeArgs p) {
+  extern __shared__ __align__(16) char lds[];
+  f32x16 acc[fast::WM][fast::WN];
+  const int n_at = p.a_rows / TILE, n_bt = p.b_rows / TILE;
+  const int b0 = (blockIdx.x % n_bt) * TILE;
+  float keep = 0.f;
+  if constexpr (MODE == PROBE_MFMA) {
+    // fragments: 16 bytes per lane straight from global memory, then registers only
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    bf16x8 fa[fast::WM], fb[fast::WN];
+#pragma unroll
+    for (int i = 0; i < fast::WM; ++i)
+      fa[i] = *reinterpret_cast<const bf16x8*>(p.A + (int64_t)((wave * 4 + i) * 64 + lane) % p.a_rows * p.k_elems);
+#pragma unroll
+    for (int j = 0; j < fast::WN; ++j)
+      fb[j] = *reinterpret_cast<const bf16x8*>(p.B + (int64_t)(b0 + (wave * 4 + j) * 64 % TILE + lane) % p.b_rows * p.k_elems);
+#pragma unroll
+    for (int i = 0; i < fast::WM; ++i)
+#pragma unroll
+      for (int j = 0; j < fast::WN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    const int steps = p.tiles_per_wg * (p.k_elems / 16);       // MFMA K steps of all tiles
+    for (int s = 0; s < steps; ++s) {
+#pragma unroll
+      for (int i = 0; i < fast::WM; ++i)
+#pragma unroll
+        for (int j = 0; j < fast::WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+  } else {
+    constexpr int LB = (MODE == PROBE_LOOP_KR || MODE == PROBE_DATA_KR) ? fast::KR : fast::KC;
+    constexpr bool MF = MODE == PROBE_LOOP_KR || MODE == PROBE_LOOP_KC;
+    fast::Pipe<fast::KC, LB, MF> pipe;
+    const int64_t ld = (int64_t)p.k_elems * 2;
+    for (int t = 0; t < p.tiles_per_wg; ++t) {
+      const int a0 = ((blockIdx.x / n_bt + t) % n_at) * TILE;
+      const fast::Operand As{reinterpret_cast<const char*>(p.A), ld, a0, p.a_rows, 0};
+      if constexpr (LB == fast::KR) {
+        const fast::Operand Bs{reinterpret_cast<const char*>(p.BT) + (int64_t)b0 * 2, (int64_t)p.b_rows * 2, 0,
+                               p.k_elems, TILE * 2};
+        pipe.start(As, Bs, p.k_elems, lds);
+      } else {
+        const fast::Operand Bs{reinterpret_cast<const char*>(p.B), ld, b0, p.b_rows, 0};
+        pipe.start(As, Bs, p.k_elems, lds);
+      }
+      pipe.run(lds, acc);
+      if constexpr (MF) {
+#pragma unroll
+        for (int i = 0; i < fast::WM; ++i)
+#pragma unroll
+          for (int j = 0; j < fast::WN; ++j) {
+            float v;
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][(i * 4 + j) & 15]));
+            keep += v;
+          }
+      }
+    }
+  }
+  if constexpr (MODE == PROBE_MFMA) {
+    // one element of every accumulator block keeps every MFMA chain alive
+#pragma unroll
+    for (int i = 0; i < fast::WM; ++i)
+#pragma unroll
+      for (int j = 0; j < fast::WN; ++j) {
+        float v;
+        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][0]));
+        keep += v;
+      }
+  }
+  p.sink[(int64_t)blockIdx.x * fast::THREADS + threadIdx.x] = keep;
+}
+
+}  // namespace flce
