@@ -22,13 +22,55 @@ if ROOT not in sys.path:
 BF16_MFMA_PEAK_TFLOPS = 2516.6      # MI355X dense bf16: 256 CU x 4096 flop/clk x 2.4 GHz
 F32_MFMA_PEAK_TFLOPS = 157.3
 
-# HBM-side traffic per launch (bytes), from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this script scaled by the
-# same counters' reading for a plain 1 GiB copy (profiles/llama3_8b_pmc.txt); only for the default launch
-# configuration of the workload they were taken on, otherwise null.
-MEASURED_TRAFFIC = {
-    "llama3_8b": {"fwd_tiles": 14.365e9 + 0.568e9, "recompute": 3.447e9 + 0.477e9,
-                  "contract_dW": 3.398e9 + 0.330e9, "contract_dH": 3.631e9 + 0.115e9},
-}
+# Plain-ALU peaks of MI355X from its unit counts and clock: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations
+# per second for ordinary fp32 vector instructions (an fma counts 2 flops: 78.6 T fma/s = 157.3 TFLOP/s), a quarter
+# of that for the transcendental unit (v_exp_f32).
+VALU_LANE_OPS_PER_S = 256 * 4 * 16 * 2.4e9
+EXP_PER_S = VALU_LANE_OPS_PER_S / 4
+
+
+def device_facts():
+    """CU count and clocks of the GPU as the box reports them (rocminfo's record of the first GPU agent)."""
+    import subprocess
+    facts = {}
+    try:
+        txt = subprocess.run(["rocminfo"], capture_output=True, text=True, timeout=30).stdout
+    except Exception:
+        return facts
+    for agent in txt.split("Agent ")[1:]:
+        if "Device Type:             GPU" not in agent:
+            continue
+        for key, name in (("Marketing Name:", "marketing_name"), ("Name:", "gfx"), ("Compute Unit:", "compute_units"),
+                          ("Max Clock Freq. (MHz):", "max_engine_clock_MHz"), ("SIMDs per CU:", "simds_per_cu"),
+                          ("Wavefront Size:", "wavefront_size")):
+            for line in agent.splitlines():
+                if line.strip().startswith(key):
+                    v = line.split(":", 1)[1].strip().split("(")[0].strip()
+                    facts[name] = int(v) if v.isdigit() else v
+                    break
+        break
+    return facts
+
+
+def measured_traffic(workload, plan):
+    """Fabric-side bytes per launch of each kernel class, from profiles/<workload>_pmc.txt (rocprofv3 FETCH_SIZE and
+    WRITE_SIZE runs of this script, scaled by the same counters' reading for a plain copy).  The summary records
+    the launch plan it was taken on; if that is not the plan of this run the figures do not apply: returns ({},
+    reason) and the caller reports null."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_pmc.txt")
+    if not os.path.exists(path):
+        return {}, f"no {os.path.relpath(path, ROOT)}"
+    rec_plan, out = None, {}
+    for line in open(path):
+        if line.startswith("plan: "):
+            rec_plan = line[len("plan: "):].strip()
+        elif line.startswith("traffic_bytes_per_launch "):
+            f = line.split()
+            kv = dict(t.split("=") for t in f[2:])
+            out[f[1]] = float(kv["fetch"]) + float(kv["write"])
+    if rec_plan != plan:
+        return {}, f"{os.path.relpath(path, ROOT)} was taken on another plan ({rec_plan!r}, now {plan!r})"
+    return out, None
 
 
 def cpu_baseline(wl, x, rows):
@@ -240,11 +282,31 @@ def main():
         torch.cuda.synchronize()
     if not args.no_profile:
         B.flce_profile_enable(1)
+    # The timed region: exactly `steps` steps between two synchronisations (ms_per_step is this wall clock).  Each
+    # step is also bracketed by events on the stream the kernels run on, with one more after the forward, for
+    # the median / minimum and the forward / backward split.
+    stream = torch.cuda.current_stream()
+    split = not args.graph and args.path == "recompute"
+    marks = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        run_step()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record(stream)
+        if split:
+            st = s.forward()
+            e[1].record(stream)
+            st = st or s.backward()
+            assert st == B.FLCE_OK, B.flce_status_string(st)
+        else:
+            run_step()
+        e[2].record(stream)
+        marks.append(e)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    step_ms = sorted(e[0].elapsed_time(e[2]) for e in marks)
+    fwd_ms = sorted(e[0].elapsed_time(e[1]) for e in marks) if split else None
+    bwd_ms = sorted(e[1].elapsed_time(e[2]) for e in marks) if split else None
+    med = lambda v: v[len(v) // 2]
     prof_ms, prof_n = {}, {}
     if not args.no_profile:
         _, prof_ms, prof_n = B.flce_profile_collect()
@@ -274,16 +336,31 @@ def main():
     for k in ("fwd_epilogue", "bwd_prep", "scale"):
         if prof_n.get(k):
             kernels[k] = {"ms_per_step": prof_ms[k] / args.steps, "launches_per_step": prof_n[k] / args.steps}
+    plan = B.flce_plan_describe(wl.N, wl.d, wl.V, s.dt)
+    traffic, why_not = measured_traffic(wl.name, plan)
+    if why_not:
+        print(f"bench.py: roofline.traffic is null: {why_not}", file=sys.stderr)
     roofline = None
     if kernels:
         dom = max(class_flops, key=lambda k: kernels.get(k, {}).get("ms_per_step", 0.0))
         a = kernels[dom]["tflops"]
         roofline = {"bound": "mfma", "kernel": dom, "achieved": a, "peak": peak, "unit": "TFLOP/s", "frac": a / peak,
-                    "traffic": (MEASURED_TRAFFIC.get(wl.name, {}).get(dom)
-                                if not any(os.environ.get(k) for k in ("FLCE_VC_TILES", "FLCE_NC_TILES", "FLCE_WINDOWS",
-                                                                       "FLCE_GENERIC")) else None),
+                    "traffic": traffic.get(dom),
                     "flops_per_launch": class_flops[dom] * wl.N * wl.d * wl.V / kernels[dom]["launches_per_step"],
                     "avg_launch_ms": kernels[dom]["ms_per_step"] / kernels[dom]["launches_per_step"]}
+    # The other roof of this path: the softmax work runs on the plain vector ALUs while the matrix pipe waits (one
+    # wavefront per SIMD), so its time adds to the MFMA time instead of hiding behind it.  Per logit: one exponential
+    # in the forward and one in the recompute, and about 10 ordinary vector instructions in each of the two.
+    n_logits = float(wl.N) * wl.V
+    alu_ms = (2.0 * n_logits / EXP_PER_S + 20.0 * n_logits / VALU_LANE_OPS_PER_S) * 1e3
+    mfma_ms = flops / (peak * 1e12) * 1e3
+    alu_roof = {"bound": "alu", "exp_per_step": 2.0 * n_logits, "vector_lane_ops_per_step": 20.0 * n_logits,
+                "peak_exp_per_s": EXP_PER_S, "peak_vector_lane_ops_per_s": VALU_LANE_OPS_PER_S,
+                "ms_at_alu_peak": alu_ms, "ms_at_mfma_peak": mfma_ms,
+                "frac_of_step_at_peaks": {"alu": alu_ms / ms_per_step, "mfma": mfma_ms / ms_per_step}}
+    props = torch.cuda.get_device_properties(0)
+    device = {"name": props.name, "compute_units": props.multi_processor_count, "hbm_bytes": props.total_memory,
+              "host_cores": os.cpu_count(), "rocminfo": device_facts()}
 
     rows = args.oracle_rows
     if rows is None:
@@ -297,20 +374,26 @@ def main():
     out = {
         "metric": "fused linear-CE fwd+bwd tokens/sec", "value": wl.N / (ms_per_step * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": med(step_ms), "ms_per_step_min": step_ms[0],
+        "forward_ms_median": med(fwd_ms) if split else None, "forward_ms_min": fwd_ms[0] if split else None,
+        "backward_ms_median": med(bwd_ms) if split else None, "backward_ms_min": bwd_ms[0] if split else None,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "d": wl.d, "V": wl.V, "reduction": wl.reduction,
                    "targets": wl.targets, "ignore_frac": wl.ignore_frac, "seed": wl.seed, "path": args.path, "launch": "graph replay" if args.graph else "eager"},
         "tflops_8NdV": tflops, "frac_of_mfma_peak": tflops / peak,
         "tflops_executed": flops_executed / (ms_per_step * 1e-3) / 1e12,
+        "frac_of_mfma_peak_executed": flops_executed / (ms_per_step * 1e-3) / 1e12 / peak,
         "flops_note": "8NdV counts the ignored rows too; the backward skips them (their rows of G are zero), "
                       "so executed flops are 2NdV + 6*rows_counted*d*V",
         "loss": loss, "n_valid": n_valid,
         "memory": {"peak_allocated_bytes": int(torch.cuda.max_memory_allocated()),
                    "path_tensor_bytes": int(s.tensor_bytes()), "workspace_bytes": int(s.ws.numel()),
                    "naive_fp32_logits_bytes": int(wl.naive_logits_bytes),
-                   "peak_over_naive_logits": torch.cuda.max_memory_allocated() / wl.naive_logits_bytes},
-        "roofline": roofline, "kernels": kernels, "cpu_baseline": base,
+                   "peak_over_naive_logits": torch.cuda.max_memory_allocated() / wl.naive_logits_bytes,
+                   "workspace_over_naive_logits": s.ws.numel() / wl.naive_logits_bytes},
+        "roofline": roofline, "alu_roofline": alu_roof, "kernels": kernels, "cpu_baseline": base,
+        "plan": plan, "device": device,
     }
     print(json.dumps(out))
 

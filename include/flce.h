@@ -50,7 +50,8 @@
  * rounding, and the bit pattern, depend on it:
  *   FLCE_WINDOWS    vocabulary windows of the forward (Section 3.2.1); 0 / unset = automatic
  *                   (at least 4, enough row block x window workgroups to cover 256 CUs).
- *   FLCE_VC_TILES   largest vocabulary chunk of the backward, in 256-row tiles (default 128).
+ *   FLCE_VC_TILES   largest vocabulary chunk of the backward, in 256-row tiles; 0 / unset = automatic
+ *                   (128; up to 512 when there are fewer than 32 token tiles, same staging bytes).
  *   FLCE_NC_TILES   largest token chunk of the backward, in 256-row tiles (default 128).
  *                   The staging buffer for G holds one chunk pair: at most VC x NC tiles.
  *   FLCE_SPLITK_DH, FLCE_SPLITK_DW
@@ -100,6 +101,14 @@ const char* flce_status_string(flce_status s);
  * buffers: there is no N*V term.  Host call, touches no device.
  */
 size_t flce_workspace_bytes(int64_t N, int64_t d, int64_t V, flce_dtype dt, int for_backward);
+
+/*
+ * Writes a one-line description of the launch plan at this shape (library version, main loop, windows,
+ * chunk counts x largest chunk in 256-row tiles, K slices, staging and workspace bytes) into `buf`; returns
+ * the length it needs (as snprintf) or -1 for an invalid shape.  Reports and profile summaries carry it, so
+ * that a measurement can be matched to the plan it was taken on.  Host call.
+ */
+int flce_plan_describe(int64_t N, int64_t d, int64_t V, flce_dtype dt, char* buf, size_t buf_bytes);
 
 /*
  * Forward (Alg. 1 over tiles, Section 3.2.1 windows + merging epilogue).

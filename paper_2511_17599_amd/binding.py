@@ -19,7 +19,7 @@ FLCE_DTYPE_BF16, FLCE_DTYPE_F32 = 0, 1
 FLCE_REDUCE_MEAN, FLCE_REDUCE_SUM = 0, 1
 FLCE_STATIC_SCRATCH_BYTES = 16 << 20
 
-EXPORTS = ("flce_version", "flce_tuning_reload", "flce_status_string", "flce_workspace_bytes", "flce_forward", "flce_backward", "flce_forward_static",
+EXPORTS = ("flce_version", "flce_tuning_reload", "flce_status_string", "flce_workspace_bytes", "flce_plan_describe", "flce_forward", "flce_backward", "flce_forward_static",
            "flce_forward_with_grads", "flce_scale", "flce_forward_rows", "flce_backward_rows", "flce_forward_partial", "flce_merge_workspace_bytes",
            "flce_merge_partials", "flce_backward_partial", "flce_last_device_status", "flce_profile_enable",
            "flce_profile_collect", "flce_probe")
@@ -44,6 +44,8 @@ def lib():
         L.flce_status_string.argtypes = [c.c_int]
         L.flce_workspace_bytes.restype = c.c_size_t
         L.flce_workspace_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_int]
+        L.flce_plan_describe.restype = c.c_int
+        L.flce_plan_describe.argtypes = [c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_char_p, c.c_size_t]
         L.flce_forward.restype = c.c_int
         L.flce_forward.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_int64,
                                    c.c_int, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
@@ -127,6 +129,14 @@ def flce_status_string(status):
 
 def flce_workspace_bytes(N, d, V, dt, for_backward):
     return int(lib().flce_workspace_bytes(N, d, V, dt, int(bool(for_backward))))
+
+
+def flce_plan_describe(N, d, V, dt):
+    buf = ctypes.create_string_buffer(512)
+    n = lib().flce_plan_describe(N, d, V, dt, buf, len(buf))
+    if n < 0:
+        raise ValueError("unsupported shape")
+    return buf.value.decode()
 
 
 def flce_forward(H, W, targets, N, d, V, ignore_index, reduction, dt, loss_out, lse_out, workspace, workspace_bytes,

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdio>
 #include <cstdlib>
 #include <mutex>
 #include <vector>
@@ -49,7 +50,7 @@ Tuning g_tuning;
 Tuning read_tuning_from_env() {
   Tuning t;
   t.windows = env_int("FLCE_WINDOWS", 0, 0, 1 << 16);
-  t.vc_tiles = env_int("FLCE_VC_TILES", 128, 1, 4096);
+  t.vc_tiles = env_int("FLCE_VC_TILES", 0, 0, 4096);
   t.nc_tiles = env_int("FLCE_NC_TILES", 128, 1, 4096);
   t.splitk_dh = env_int("FLCE_SPLITK_DH", 0, 0, 16);
   t.splitk_dw = env_int("FLCE_SPLITK_DW", 0, 0, 16);
@@ -126,8 +127,17 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p, bool all
   const int64_t fwd_fixed = o;
 
   // Backward staging: a fixed-size G tile of at most vc x nc 256-tiles.
-  const int vc_max = tn.vc_tiles;
   const int nc_max = tn.nc_tiles;
+  // Automatic vocabulary chunk: 128 tiles; with few token rows the same staging bytes reach further along the
+  // vocabulary (at most 128 x 32 tiles of G, 512 MiB in bf16, up to 512 vocabulary tiles), which saves whole
+  // launches and the fp32 running sum of dH on short-sequence shapes.  Kept within a buffer descriptor's reach.
+  int vc_max = tn.vc_tiles;
+  if (vc_max == 0) {
+    const int64_t nct = std::min<int64_t>(p.n_rb, nc_max);
+    vc_max = (int)std::max<int64_t>(128, std::min<int64_t>(512, 4096 / nct));
+    const int64_t reach = (((int64_t)1 << 32) / (d * p.esize) - 64) / TILE;
+    if (vc_max > 128 && reach < vc_max) vc_max = (int)std::max<int64_t>(128, reach);
+  }
   // Chunks of the full size plus a remainder, so that launches of full chunks come out in whole rounds of 256
   // workgroups (128 tiles times any even tile count); an even split only when the remainder would be a sliver.
   auto chunking = [](int tiles, int cmax, int& n_chunks, int& chunk) {
@@ -444,7 +454,8 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
       {
         const RecomputeArgs<T> rc = recompute_args(vc, nc, G);
         ProfScope ps(FLCE_PROF_RECOMPUTE, st);
-        const int grid = rc.n_nt * rc.n_vt;
+        // at most one workgroup per CU: each walks its share of the chunk's tiles
+        const int grid = L::TRANSPOSING ? std::min(rc.n_nt * rc.n_vt, NUM_CU) : rc.n_nt * rc.n_vt;
         if (hkr) {
           if constexpr (L::TRANSPOSING) {
             if (rows.grad_rows) recompute_kernel<T, L, true, true><<<grid, L::THREADS, L::LDS, st>>>(rc);
@@ -459,7 +470,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
         const ContractArgs<T> a = dw_args(vc, nc, G);
         ProfScope ps(FLCE_PROF_CONTRACT_DW, st);
         if constexpr (L::TRANSPOSING)
-          contract_kernel<T, L, OPS_DW_TR><<<a.n_nt * a.n_mt * a.n_split, L::THREADS, L::LDS, st>>>(a);
+          contract_kernel<T, L, OPS_DW_TR><<<std::min(a.n_nt * a.n_mt * a.n_split, NUM_CU), L::THREADS, L::LDS, st>>>(a);
         else
           contract_kernel<T, L, OPS_KC><<<a.n_nt * a.n_mt * a.n_split, L::THREADS, L::LDS, st>>>(a);
         if (a.n_split > 1) splitk_reduce_kernel<T><<<a.n_nt * TILE, 256, 0, st>>>(a);
@@ -468,7 +479,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
         const ContractArgs<T> a = dh_args(vc, nc, G);
         ProfScope ps(FLCE_PROF_CONTRACT_DH, st);
         if constexpr (L::TRANSPOSING)
-          contract_kernel<T, L, OPS_DH_TR><<<a.n_nt * a.n_mt * a.n_split, L::THREADS, L::LDS, st>>>(a);
+          contract_kernel<T, L, OPS_DH_TR><<<std::min(a.n_nt * a.n_mt * a.n_split, NUM_CU), L::THREADS, L::LDS, st>>>(a);
         else
           contract_kernel<T, L, OPS_KC><<<a.n_nt * a.n_mt * a.n_split, L::THREADS, L::LDS, st>>>(a);
         if (a.n_split > 1) splitk_reduce_kernel<T><<<a.n_nt * TILE, 256, 0, st>>>(a);
@@ -537,6 +548,18 @@ const char* flce_status_string(flce_status s) {
     case FLCE_ERR_HIP: return "HIP runtime error";
   }
   return "unknown status";
+}
+
+int flce_plan_describe(int64_t N, int64_t d, int64_t V, flce_dtype dt, char* buf, size_t buf_bytes) {
+  flce::Plan p;
+  if (!buf || buf_bytes == 0 || !flce::make_plan(N, d, V, dt, p)) return -1;
+  return std::snprintf(buf, buf_bytes,
+                       "flce %s loop=%s h_copy=%d windows=%d vocab_chunks=%dx%d row_chunks=%dx%d splitk_dH=%d splitk_dW=%d "
+                       "staging_bytes=%lld fwd_ws=%lld bwd_ws=%lld",
+                       flce_version(), p.fast ? "tuned" : "generic", p.hkr ? 1 : 0, p.n_win, p.n_vch, p.vc_tiles, p.n_nch,
+                       p.nc_tiles, p.split_dh, p.split_dw,
+                       (long long)((int64_t)p.nc_tiles * flce::TILE * p.ld_v * p.esize), (long long)p.fwd_bytes,
+                       (long long)p.bwd_bytes);
 }
 
 size_t flce_workspace_bytes(int64_t N, int64_t d, int64_t V, flce_dtype dt, int for_backward) {

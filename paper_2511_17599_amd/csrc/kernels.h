@@ -602,43 +602,83 @@ struct RecomputeArgs {
   const float* gam_c; float onehot_weight; float uniform_part;   // 1 - eps, eps / V
 };
 
-// One tile of the recompute step; `bid` of `nblocks` tiles of this launch.
+// Per-row inputs of a recompute tile, one set per token column a lane owns.
+template <typename L>
+struct RowMeta {
+  int tgt[L::WN];       // target column inside the slice, -1 for a padding row
+  float lse[L::WN];
+  float gam[L::WN];     // per-row variant only
+};
+
+// The recompute step.  The launch has min(tiles, 256) workgroups; workgroup b takes tiles b, b + gridDim.x, ... of
+// the chunk.  With the tuned loop the first K stages of a workgroup's next tile (and that tile's per-row inputs) are
+// requested before the current tile's G is formed and stored, so the latency of a tile's first operands hides behind
+// the previous tile's post-processing: it matters when the K loop is short (small d).
 // PER_ROW: g = Gamma_row * (p - (1 - eps) [v == y_row] - eps / V), the upstream gradient applied here because
 // it differs from row to row (Alg. 2 with a per-position Gamma); otherwise g = p - [v == y_row] and the
 // scalar Gamma is applied when the contractions write out.
 template <typename T, typename L, bool HKR, bool PER_ROW = false>
-__device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bid, int nblocks, char* lds) {
+__global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> a) {
+  extern __shared__ __align__(16) char lds[];
   const T* __restrict__ Hc = a.Hc; const T* __restrict__ HcT = a.HcT; const T* __restrict__ W = a.W;
-  const int* __restrict__ tgt_c = a.tgt_c; const float* __restrict__ lse_c = a.lse_c;
   const int npad = a.npad, d = a.d, V = a.V;
   T* __restrict__ G = a.G; T* __restrict__ GT = a.GT; const int64_t ldG = a.ldG, ldGT = a.ldGT;
   // Only the row tiles that hold counted rows are rastered (their number is known on the device
-  // alone), so the XCDs share the work evenly however many rows are ignored; the surplus
-  // workgroups of the launch, sized for N rows, leave at once.
-  (void)nblocks;
+  // alone), so the XCDs share the work evenly however many rows are ignored; workgroups beyond the
+  // useful tiles of a launch sized for N rows leave at once.
   const int n_nt = max(0, min(a.n_nt, ((int)a.hdr->n_valid - a.nt0 * TILE + TILE - 1) / TILE));
   const int useful = n_nt * a.n_vt;
-  if (bid >= useful) return;
-  const int id = xcd_contiguous_id(bid, useful);
-  int p, q;                                    // row tile, vocabulary tile inside the chunk
-  grouped_raster(id, n_nt, a.n_vt, 8, p, q);
-  const int n0 = (a.nt0 + p) * TILE, v0 = (a.vt0 + q) * TILE;
+  int t = blockIdx.x;
+  if (t >= useful) return;
   const int64_t ld_bytes = (int64_t)d * sizeof(T);
-  f32x16 acc[L::WM][L::WN];
-  if constexpr (HKR) L::run_bt(W, ld_bytes, v0, V, HcT, (int64_t)npad * sizeof(T), n0, d, lds, acc);
-  else L::run(W, ld_bytes, v0, V, Hc, ld_bytes, n0, npad, (int)ld_bytes, lds, acc);
-
+  auto place = [&](int tile, int& p, int& q) {     // row tile, vocabulary tile inside the chunk
+    grouped_raster(xcd_contiguous_id(tile, useful), n_nt, a.n_vt, 8, p, q);
+  };
+  auto load_meta = [&](int n0, RowMeta<L>& m) {
 #pragma unroll
-  for (int j = 0; j < L::WN; ++j) {
-    const int nl = p * TILE + L::tile_n(j);       // row inside the staging tile
-    const int n = n0 + L::tile_n(j);
-    const int tgt = tgt_c[n];
-    // exp(z - lse) = 2^(z * log2e - lse * log2e); a padding row (tgt < 0) gets lse = +inf here, so its p is
-    // exactly 0, and no column equals its target: its row of G is 0 without a mask
-    const float ll = tgt >= 0 ? -lse_c[n] * LOG2E : NEG_INF;
-    float gam = 1.f;
-    if constexpr (PER_ROW) gam = tgt >= 0 ? a.gam_c[n] : 0.f;
-    const float unif = tgt >= 0 ? a.uniform_part : 0.f;
+    for (int j = 0; j < L::WN; ++j) {
+      const int n = n0 + L::tile_n(j);
+      m.tgt[j] = a.tgt_c[n];
+      m.lse[j] = a.lse_c[n];
+      if constexpr (PER_ROW) m.gam[j] = a.gam_c[n];
+    }
+  };
+  // Marks the point where a tile's per-row inputs must have arrived: the compiler's wait for them lands here (it
+  // cannot see the main loop's own requests, so a wait placed later would also wait for the next tile's operands).
+  auto need_meta = [&](RowMeta<L>& m) {
+#pragma unroll
+    for (int j = 0; j < L::WN; ++j) {
+      asm volatile("" : "+v"(m.tgt[j]), "+v"(m.lse[j]));
+      if constexpr (PER_ROW) asm volatile("" : "+v"(m.gam[j]));
+    }
+  };
+  typename L::template Stream<HKR> stream;
+  int p, q;
+  place(t, p, q);
+  RowMeta<L> meta;
+  if constexpr (L::TRANSPOSING) load_meta((a.nt0 + p) * TILE, meta);
+  stream.start(W, ld_bytes, (a.vt0 + q) * TILE, V, Hc, HcT, ld_bytes, (int64_t)npad * sizeof(T), (a.nt0 + p) * TILE, npad, d,
+               lds);
+  f32x16 acc[L::WM][L::WN];
+  for (;;) {
+    stream.run(lds, acc);
+    const int t_next = t + gridDim.x;
+    // (a main loop with nothing to request ahead gets one tile per workgroup)
+    const bool more = L::TRANSPOSING && t_next < useful;
+    int p_next = 0, q_next = 0;
+    RowMeta<L> meta_next;
+    if constexpr (!L::TRANSPOSING) load_meta((a.nt0 + p) * TILE, meta);   // no registers to spare across that main loop
+    need_meta(meta);
+    if (more) {
+      place(t_next, p_next, q_next);
+      load_meta((a.nt0 + p_next) * TILE, meta_next);
+      stream.start(W, ld_bytes, (a.vt0 + q_next) * TILE, V, Hc, HcT, ld_bytes, (int64_t)npad * sizeof(T),
+                   (a.nt0 + p_next) * TILE, npad, d, lds);
+    }
+
+    const int v0 = (a.vt0 + q) * TILE;
+    // Blocks in (i, j) order, i outermost: what depends on the vocabulary position only (the padding masks of a
+    // block that straddles the vocabulary's end) is then shared by the four j of one i and dies with it.
 #pragma unroll
     for (int i = 0; i < L::WM; ++i) {
       // All 32 vocabulary positions of a block belong to one wavefront: "behind the vocabulary's end" and
@@ -646,38 +686,47 @@ __device__ __forceinline__ void recompute_tile(const RecomputeArgs<T>& a, int bi
       const int blk0 = v0 + __builtin_amdgcn_readfirstlane(L::tile_m(i, 0) & ~31);
       const bool whole = blk0 + 32 <= V;
 #pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const int mloc = L::tile_m(i, rq * 4);    // first of 4 consecutive vocabulary positions
-        float g[4];
+      for (int j = 0; j < L::WN; ++j) {
+        const int nl = p * TILE + L::tile_n(j);       // row inside the staging tile
+        const int tgt = meta.tgt[j];
+        // exp(z - lse) = 2^(z * log2e - lse * log2e); a padding row (tgt < 0) gets lse = +inf here, so its p is
+        // exactly 0, and no column equals its target: its row of G is 0 without a mask
+        const float ll = tgt >= 0 ? -meta.lse[j] * LOG2E : NEG_INF;
+        float gam = 1.f;
+        if constexpr (PER_ROW) gam = tgt >= 0 ? meta.gam[j] : 0.f;
+        const float unif = tgt >= 0 ? a.uniform_part : 0.f;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int v = v0 + mloc + e;
-          float pz = fast_exp2(fmaf(L::acc_get(acc[i][j], rq * 4 + e), LOG2E, ll));
-          if constexpr (PER_ROW) pz = gam * (pz - ((v == tgt) ? a.onehot_weight : 0.f) - unif);
-          else pz -= (v == tgt) ? 1.f : 0.f;
-          g[e] = pz;
-        }
-        if (!whole) {
+        for (int rq = 0; rq < 4; ++rq) {
+          const int mloc = L::tile_m(i, rq * 4);    // first of 4 consecutive vocabulary positions
+          float g[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (v0 + mloc + e >= V) g[e] = 0.f;
-        }
-        const int vl = q * TILE + mloc;
-        Pack4<T>::store(G + (int64_t)nl * ldG + vl, g[0], g[1], g[2], g[3]);
-        if (!L::TRANSPOSING) {
+          for (int e = 0; e < 4; ++e) {
+            const int v = v0 + mloc + e;
+            float pz = fast_exp2(fmaf(L::acc_get(acc[i][j], rq * 4 + e), LOG2E, ll));
+            if constexpr (PER_ROW) pz = gam * (pz - ((v == tgt) ? a.onehot_weight : 0.f) - unif);
+            else pz -= (v == tgt) ? 1.f : 0.f;
+            g[e] = pz;
+          }
+          if (!whole) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) GT[(int64_t)(vl + e) * ldGT + nl] = Pack4<T>::one(g[e]);
+            for (int e = 0; e < 4; ++e)
+              if (v0 + mloc + e >= V) g[e] = 0.f;
+          }
+          const int vl = q * TILE + mloc;
+          Pack4<T>::store(G + (int64_t)nl * ldG + vl, g[0], g[1], g[2], g[3]);
+          if (!L::TRANSPOSING) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) GT[(int64_t)(vl + e) * ldGT + nl] = Pack4<T>::one(g[e]);
+          }
         }
+        __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
       }
-      __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
     }
+    if (!more) break;
+    need_meta(meta_next);
+    t = t_next; p = p_next; q = q_next;
+    meta = meta_next;
   }
-}
-
-template <typename T, typename L, bool HKR, bool PER_ROW = false>
-__global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> a) {
-  extern __shared__ __align__(16) char lds[];
-  recompute_tile<T, L, HKR, PER_ROW>(a, blockIdx.x, gridDim.x, lds);
 }
 
 // ------------------------------------------------------------------------------------
@@ -713,93 +762,132 @@ struct ContractArgs {
   int n_split, k_split; float* partial; int64_t partial_stride;
 };
 
-template <typename T, typename L, int OPS>
-__device__ __forceinline__ void contract_tile(const ContractArgs<T>& a, int bid, int nblocks, char* lds) {
-  const T* __restrict__ A = a.A; const T* __restrict__ B = a.B;
-  const int64_t lda = a.lda, ldb = a.ldb;
-  const int a_krows = a.a_krows, d = a.d, b_rows = a.b_rows, k_start = a.k_start, acc_row0 = a.acc_row0;
-  const int out_row0 = a.out_row0, out_rows = a.out_rows, mean = a.mean;
-  int flags = a.flags;
-  int k_elems = a.k_elems;
-  float* __restrict__ accbuf = a.accbuf; T* __restrict__ out = a.out;
-  const Header* __restrict__ hdr = a.hdr; const int* __restrict__ rowmap = a.rowmap;
-  const float grad_loss = a.grad_loss;
-  (void)nblocks;
-  const int nv = (int)hdr->n_valid;
-  // With compacted output rows only the row tiles that hold counted rows are rastered, so the
-  // XCDs share the work evenly; surplus workgroups of the launch leave at once.
-  int n_nt = a.n_nt;
-  if (flags & ROWS_COMPACT) n_nt = max(0, min(n_nt, (nv - out_row0 + TILE - 1) / TILE));
-  const int tiles = n_nt * a.n_mt;
-  if (tiles == 0) return;
-  const int z = bid / tiles;                                 // K slice of this workgroup
-  if (z >= max(1, a.n_split)) return;
-  const int id = xcd_contiguous_id(bid - z * tiles, tiles);
-  int p, q;                                    // output-row tile, hidden tile
-  grouped_raster(id, n_nt, a.n_mt, 8, p, q);
-  if (flags & K_COMPACT) k_elems = max(0, min(k_elems, (nv - k_start + TILE - 1) / TILE * TILE));
-  int k0 = 0;
-  if (a.n_split > 1) {
-    k0 = z * a.k_split;
-    k_elems = max(0, min(a.k_split, k_elems - k0));
-    accbuf = a.partial + (int64_t)z * a.partial_stride;
-    flags = (flags & ROWS_COMPACT) | WRITE_ACC;
-  }
-  f32x16 acc[L::WM][L::WN];
-  if constexpr (OPS == OPS_KC) {
-    L::run(A + k0, lda * (int64_t)sizeof(T), q * TILE, d, B + k0, ldb * (int64_t)sizeof(T), p * TILE, b_rows,
-           k_elems * (int)sizeof(T), lds, acc);
-  } else {
-    // A: K rows start at A (a_krows valid from there), window of 256 hidden columns at q
-    const int width = max(0, min(TILE, d - q * TILE)) * 2;
-    const fast::Operand As{reinterpret_cast<const char*>(A + (int64_t)k0 * lda) + (int64_t)q * TILE * 2, lda * 2, 0,
-                           a_krows - k0, width};
-    if constexpr (OPS == OPS_DH_TR) {
-      const fast::Operand Bs{reinterpret_cast<const char*>(B + k0), ldb * 2, p * TILE, b_rows, 0};
-      fast::mainloop<fast::KR, fast::KC>(As, Bs, k_elems, lds, acc);
-    } else {
-      const fast::Operand Bs{reinterpret_cast<const char*>(B + (int64_t)k0 * ldb) + (int64_t)p * TILE * 2, ldb * 2, 0,
-                             b_rows - k0, TILE * 2};
-      fast::mainloop<fast::KR, fast::KR>(As, Bs, k_elems, lds, acc);
-    }
-  }
-
-  float scale = grad_loss;
-  if (mean) scale = nv > 0 ? grad_loss / (float)nv : 0.f;
-#pragma unroll
-  for (int j = 0; j < L::WN; ++j) {
-    const int n = out_row0 + p * TILE + L::tile_n(j);
-    if (n >= out_rows) continue;
-    int64_t orow = n;
-    if (flags & ROWS_COMPACT) {
-      orow = rowmap[n];
-      if (orow < 0) continue;
-    }
-#pragma unroll
-    for (int i = 0; i < L::WM; ++i)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const int m = q * TILE + L::tile_m(i, rq * 4);
-        if (m >= d) continue;
-        f32x4 v = {L::acc_get(acc[i][j], rq * 4), L::acc_get(acc[i][j], rq * 4 + 1), L::acc_get(acc[i][j], rq * 4 + 2),
-                   L::acc_get(acc[i][j], rq * 4 + 3)};
-        float* ap = accbuf + (int64_t)(n - acc_row0) * d + m;
-        if (flags & READ_ACC) v += *reinterpret_cast<const f32x4*>(ap);
-        if (flags & WRITE_ACC) *reinterpret_cast<f32x4*>(ap) = v;
-        if (flags & WRITE_OUT) {
-          // "+ 0.f" turns a -0 product into +0
-          Pack4<T>::store(out + orow * d + m, v[0] * scale + 0.f, v[1] * scale + 0.f, v[2] * scale + 0.f,
-                          v[3] * scale + 0.f);
-        }
-        if (rq == 3) __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
-      }
-  }
-}
-
+// With the tuned loop a launch has at most 256 workgroups; workgroup b takes work items b, b + gridDim.x, ... (an
+// item = one output tile of one K slice) and requests the first K stages of its next item before it writes out the
+// current one, as the recompute step does.
 template <typename T, typename L, int OPS>
 __global__ __launch_bounds__(L::THREADS) void contract_kernel(ContractArgs<T> a) {
   extern __shared__ __align__(16) char lds[];
-  contract_tile<T, L, OPS>(a, blockIdx.x, gridDim.x, lds);
+  const T* __restrict__ A = a.A; const T* __restrict__ B = a.B;
+  const int64_t lda = a.lda, ldb = a.ldb;
+  const int d = a.d;
+  T* __restrict__ out = a.out;
+  const int nv = (int)a.hdr->n_valid;
+  // With compacted output rows only the row tiles that hold counted rows are rastered, so the
+  // XCDs share the work evenly; surplus workgroups of the launch leave at once.
+  int n_nt = a.n_nt;
+  if (a.flags & ROWS_COMPACT) n_nt = max(0, min(n_nt, (nv - a.out_row0 + TILE - 1) / TILE));
+  const int tiles = n_nt * a.n_mt;
+  const int n_split = max(1, a.n_split);
+  const int total = tiles * n_split;
+  int b = blockIdx.x;
+  if (b >= total) return;
+  int k_all = a.k_elems;
+  if (a.flags & K_COMPACT) k_all = max(0, min(k_all, (nv - a.k_start + TILE - 1) / TILE * TILE));
+  float scale = a.grad_loss;
+  if (a.mean) scale = nv > 0 ? a.grad_loss / (float)nv : 0.f;
+
+  // item -> K slice z, output-row tile p, hidden tile q; K range [k0, k0 + k_elems) of the slice
+  auto place = [&](int item, int& z, int& p, int& q, int& k0, int& k_elems) {
+    z = item / tiles;
+    grouped_raster(xcd_contiguous_id(item - z * tiles, tiles), n_nt, a.n_mt, 8, p, q);
+    k0 = 0; k_elems = k_all;
+    if (a.n_split > 1) { k0 = z * a.k_split; k_elems = max(0, min(a.k_split, k_all - k0)); }
+  };
+  // output rows of the lane's token columns: the original row of a compact row, -1 = nothing to write
+  auto load_rows = [&](int p, int64_t (&orow)[L::WN]) {
+#pragma unroll
+    for (int j = 0; j < L::WN; ++j) {
+      const int n = a.out_row0 + p * TILE + L::tile_n(j);
+      orow[j] = -1;
+      if (n < a.out_rows) orow[j] = (a.flags & ROWS_COMPACT) ? (int64_t)a.rowmap[n] : (int64_t)n;
+    }
+  };
+  auto need_rows = [&](int64_t (&orow)[L::WN]) {     // the compiler's wait for the loads above lands here
+#pragma unroll
+    for (int j = 0; j < L::WN; ++j) asm volatile("" : "+v"(orow[j]));
+  };
+  // Running sum / Gamma / rounding of one finished tile.
+  auto flush = [&](f32x16 (&acc)[L::WM][L::WN], int z, int p, int q, const int64_t (&orow)[L::WN]) {
+    int flags = a.flags;
+    float* __restrict__ accbuf = a.accbuf;
+    if (a.n_split > 1) {
+      accbuf = a.partial + (int64_t)z * a.partial_stride;
+      flags = (flags & ROWS_COMPACT) | WRITE_ACC;
+    }
+#pragma unroll
+    for (int j = 0; j < L::WN; ++j) {
+      if (orow[j] < 0) continue;
+      const int n = a.out_row0 + p * TILE + L::tile_n(j);
+#pragma unroll
+      for (int i = 0; i < L::WM; ++i)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          const int m = q * TILE + L::tile_m(i, rq * 4);
+          if (m >= d) continue;
+          f32x4 v = {L::acc_get(acc[i][j], rq * 4), L::acc_get(acc[i][j], rq * 4 + 1), L::acc_get(acc[i][j], rq * 4 + 2),
+                     L::acc_get(acc[i][j], rq * 4 + 3)};
+          float* ap = accbuf + (int64_t)(n - a.acc_row0) * d + m;
+          if (flags & READ_ACC) v += *reinterpret_cast<const f32x4*>(ap);
+          if (flags & WRITE_ACC) *reinterpret_cast<f32x4*>(ap) = v;
+          if (flags & WRITE_OUT) {
+            // "+ 0.f" turns a -0 product into +0
+            Pack4<T>::store(out + orow[j] * d + m, v[0] * scale + 0.f, v[1] * scale + 0.f, v[2] * scale + 0.f,
+                            v[3] * scale + 0.f);
+          }
+          if (rq == 3) __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
+        }
+    }
+  };
+
+  f32x16 acc[L::WM][L::WN];
+  int z, p, q, k0, k_elems;
+  place(b, z, p, q, k0, k_elems);
+  int64_t orow[L::WN];
+  if constexpr (OPS == OPS_KC) {
+    // one item per workgroup: this main loop has nothing to request ahead
+    L::run(A + k0, lda * (int64_t)sizeof(T), q * TILE, d, B + k0, ldb * (int64_t)sizeof(T), p * TILE, a.b_rows,
+           k_elems * (int)sizeof(T), lds, acc);
+    load_rows(p, orow);
+    flush(acc, z, p, q, orow);
+  } else {
+    fast::Pipe<fast::KR, OPS == OPS_DH_TR ? fast::KC : fast::KR> pipe;
+    auto start = [&](int p, int q, int k0, int k_elems) {
+      // A: K rows start at A (a_krows valid from there), window of 256 hidden columns at q
+      const int width = max(0, min(TILE, d - q * TILE)) * 2;
+      const fast::Operand As{reinterpret_cast<const char*>(A + (int64_t)k0 * lda) + (int64_t)q * TILE * 2, lda * 2, 0,
+                             a.a_krows - k0, width};
+      if constexpr (OPS == OPS_DH_TR) {
+        const fast::Operand Bs{reinterpret_cast<const char*>(B + k0), ldb * 2, p * TILE, a.b_rows, 0};
+        pipe.start(As, Bs, k_elems, lds);
+      } else {
+        const fast::Operand Bs{reinterpret_cast<const char*>(B + (int64_t)k0 * ldb) + (int64_t)p * TILE * 2, ldb * 2,
+                               0, a.b_rows - k0, TILE * 2};
+        pipe.start(As, Bs, k_elems, lds);
+      }
+    };
+    load_rows(p, orow);
+    start(p, q, k0, k_elems);
+    for (;;) {
+      pipe.run(lds, acc);
+      const int b_next = b + gridDim.x;
+      const bool more = b_next < total;
+      int z_next = 0, p_next = 0, q_next = 0, k0_next = 0, k_next = 0;
+      int64_t orow_next[L::WN];
+      need_rows(orow);
+      if (more) {
+        place(b_next, z_next, p_next, q_next, k0_next, k_next);
+        load_rows(p_next, orow_next);
+        start(p_next, q_next, k0_next, k_next);
+      }
+      flush(acc, z, p, q, orow);
+      if (!more) break;
+      need_rows(orow_next);
+      b = b_next; z = z_next; p = p_next; q = q_next;
+#pragma unroll
+      for (int j = 0; j < L::WN; ++j) orow[j] = orow_next[j];
+    }
+  }
 }
 
 // Second half of a split-K contraction: one block per output row of the launch; adds the K

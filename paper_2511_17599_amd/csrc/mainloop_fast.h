@@ -223,6 +223,10 @@ struct Pipe {
     fa.init(wave >> 1);
     fb.init(wave & 1);
     lds_wave = wave * 4096;
+    // Opaque to the optimiser: in a kernel that walks several tiles these two are loop invariant, and everything
+    // derived from them (a dozen comparisons of the K count, the LDS address of every request of every stage)
+    // would be precomputed once and kept alive in scalar registers across the whole tile loop, which overflows them.
+    asm volatile("" : "+s"(KT), "+s"(lds_wave));
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
       if (s < KT) {
