@@ -72,6 +72,8 @@ struct GenericLoop {      // any dtype, any K that is a multiple of 16 bytes; 8 
 struct FastLoop {         // bf16, K a multiple of 32 elements; 4 wavefronts 2 x 2, global -> LDS DMA
   static constexpr int THREADS = fast::THREADS, WM = fast::WM, WN = fast::WN, LDS = fast::LDS_BYTES;
   static constexpr bool TRANSPOSING = true;   // can take an operand whose K index runs over memory rows
+  // LDS that post-processing may use while the next tile's first three K stages are being filled: the fourth stage
+  static constexpr int FREE_LDS_OFFSET = (fast::NS - 1) * fast::STAGE, FREE_LDS_BYTES = fast::STAGE;
   static __device__ __forceinline__ int tile_m(int i, int r) { return fast::tile_m(i, r); }
   static __device__ __forceinline__ int tile_n(int j) { return fast::tile_n(j); }
   static __device__ __forceinline__ int slot() { return fast::slot_of_lane(); }
@@ -677,6 +679,73 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
     }
 
     const int v0 = (a.vt0 + q) * TILE;
+    if constexpr (L::TRANSPOSING) {
+      // Tuned loop.  A lane holds, of 32 token rows x 128 vocabulary positions per j, scattered 8-byte pieces of one
+      // row; stored as they lie, every store instruction would touch 64 different memory rows.  Each wavefront
+      // therefore passes its 32 x 128 piece (8 KiB of bf16) through its own slice of the free LDS stage and writes
+      // whole 256-byte runs: 16 lanes per row, 4 rows per instruction.  LDS row = 256 bytes, its 16-byte chunks
+      // XOR-ed with the row number so that neither the 8-byte writes nor the 16-byte reads collide on banks.
+      static_assert(sizeof(T) == 2 && L::WM == 4 && L::WN == 4, "tuned epilogue is laid out for bf16 128 x 128 wave tiles");
+      const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+      char* stage = lds + L::FREE_LDS_OFFSET + wave * 8192;
+      const int wrow = lane & 31, whalf = lane >> 5;              // writer: token row of the piece, lane half
+      const int rrow = lane >> 4, rchunk = lane & 15;             // reader: row within a group of 4, 16-byte chunk
+      const int vbase = v0 + (wave >> 1) * 128;                   // first vocabulary position of the piece
+#pragma unroll
+      for (int j = 0; j < L::WN; ++j) {
+        const int tgt = meta.tgt[j];
+        // exp(z - lse) = 2^(z * log2e - lse * log2e); a padding row (tgt < 0) gets lse = +inf here, so its p is
+        // exactly 0, and no column equals its target: its row of G is 0 without a mask
+        const float ll = tgt >= 0 ? -meta.lse[j] * LOG2E : NEG_INF;
+        float gam = 1.f;
+        if constexpr (PER_ROW) gam = tgt >= 0 ? meta.gam[j] : 0.f;
+        const float unif = tgt >= 0 ? a.uniform_part : 0.f;
+#pragma unroll
+        for (int i = 0; i < L::WM; ++i) {
+          const int blk0 = vbase + i * 32;                        // wave-uniform
+          const bool whole = blk0 + 32 <= V;
+          // Does any token column of this wavefront have its target among the block's 32 vocabulary positions?
+          // Almost never (32 of V positions), and then the one-hot term costs nothing: a wave-uniform branch.
+          const bool hit = __ballot((unsigned)(tgt - blk0) < 32u) != 0ull;
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            const int vpos = blk0 + rq * 8 + whalf * 4;           // first of this lane's 4 consecutive positions
+            float g[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) g[e] = fast_exp2(fmaf(L::acc_get(acc[i][j], rq * 4 + e), LOG2E, ll));
+            if (hit) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (vpos + e == tgt) g[e] -= PER_ROW ? a.onehot_weight : 1.f;
+            }
+            if constexpr (PER_ROW) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) g[e] = gam * (g[e] - unif);
+            }
+            if (!whole) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (vpos + e >= V) g[e] = 0.f;
+            }
+            uint2 packed;
+            packed.x = f32x2_to_bf16x2_bits(g[0], g[1]);
+            packed.y = f32x2_to_bf16x2_bits(g[2], g[3]);
+            const int chunk = (i * 4 + rq) ^ (wrow & 15);
+            *reinterpret_cast<uint2*>(stage + wrow * 256 + chunk * 16 + whalf * 8) = packed;
+          }
+          __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
+        }
+        // the piece is complete in LDS (a wavefront's LDS operations complete in order): write it out row by row
+        const int64_t row0 = (int64_t)p * TILE + (wave & 1) * 128 + j * 32;
+        T* __restrict__ gdst = G + row0 * ldG + q * TILE + (wave >> 1) * 128 + rchunk * 8;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int r = k * 4 + rrow;
+          const u32x4 vq = *reinterpret_cast<const u32x4*>(stage + r * 256 + ((rchunk ^ (r & 15)) * 16));
+          *reinterpret_cast<u32x4*>(gdst + (int64_t)r * ldG) = vq;
+        }
+      }
+    } else {
     // Blocks in (i, j) order, i outermost: what depends on the vocabulary position only (the padding masks of a
     // block that straddles the vocabulary's end) is then shared by the four j of one i and dies with it.
 #pragma unroll
@@ -688,6 +757,8 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
 #pragma unroll
       for (int j = 0; j < L::WN; ++j) {
         const int nl = p * TILE + L::tile_n(j);       // row inside the staging tile
+        // this lane's first position in the row; block (i, rq) lies a constant 32 i + 8 rq further on
+        T* __restrict__ grow = G + (int64_t)nl * ldG + q * TILE + L::tile_m(0, 0);
         const int tgt = meta.tgt[j];
         // exp(z - lse) = 2^(z * log2e - lse * log2e); a padding row (tgt < 0) gets lse = +inf here, so its p is
         // exactly 0, and no column equals its target: its row of G is 0 without a mask
@@ -695,17 +766,23 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
         float gam = 1.f;
         if constexpr (PER_ROW) gam = tgt >= 0 ? meta.gam[j] : 0.f;
         const float unif = tgt >= 0 ? a.uniform_part : 0.f;
+        // Does any token column of this wavefront have its target among the block's 32 vocabulary positions?
+        // Almost never (32 of V positions), and then the one-hot term costs nothing: a wave-uniform branch.
+        const bool hit = __ballot((unsigned)(tgt - blk0) < 32u) != 0ull;
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq) {
           const int mloc = L::tile_m(i, rq * 4);    // first of 4 consecutive vocabulary positions
           float g[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int v = v0 + mloc + e;
-            float pz = fast_exp2(fmaf(L::acc_get(acc[i][j], rq * 4 + e), LOG2E, ll));
-            if constexpr (PER_ROW) pz = gam * (pz - ((v == tgt) ? a.onehot_weight : 0.f) - unif);
-            else pz -= (v == tgt) ? 1.f : 0.f;
-            g[e] = pz;
+          for (int e = 0; e < 4; ++e) g[e] = fast_exp2(fmaf(L::acc_get(acc[i][j], rq * 4 + e), LOG2E, ll));
+          if (hit) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (v0 + mloc + e == tgt) g[e] -= PER_ROW ? a.onehot_weight : 1.f;
+          }
+          if constexpr (PER_ROW) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) g[e] = gam * (g[e] - unif);
           }
           if (!whole) {
 #pragma unroll
@@ -713,7 +790,7 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
               if (v0 + mloc + e >= V) g[e] = 0.f;
           }
           const int vl = q * TILE + mloc;
-          Pack4<T>::store(G + (int64_t)nl * ldG + vl, g[0], g[1], g[2], g[3]);
+          Pack4<T>::store(grow + (i * 32 + rq * 8), g[0], g[1], g[2], g[3]);
           if (!L::TRANSPOSING) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) GT[(int64_t)(vl + e) * ldGT + nl] = Pack4<T>::one(g[e]);
@@ -721,6 +798,7 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
         }
         __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
       }
+    }
     }
     if (!more) break;
     need_meta(meta_next);
@@ -819,20 +897,24 @@ __global__ __launch_bounds__(L::THREADS) void contract_kernel(ContractArgs<T> a)
     for (int j = 0; j < L::WN; ++j) {
       if (orow[j] < 0) continue;
       const int n = a.out_row0 + p * TILE + L::tile_n(j);
+      // this lane's first hidden position; block (i, rq) lies a constant 32 i + 8 rq further on
+      const int m0 = q * TILE + L::tile_m(0, 0);
+      float* __restrict__ arow = accbuf + (int64_t)(n - a.acc_row0) * d + m0;
+      T* __restrict__ orowp = out + orow[j] * d + m0;
 #pragma unroll
       for (int i = 0; i < L::WM; ++i)
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq) {
-          const int m = q * TILE + L::tile_m(i, rq * 4);
-          if (m >= d) continue;
+          const int c = i * 32 + rq * 8;
+          if (m0 + c >= d) continue;
           f32x4 v = {L::acc_get(acc[i][j], rq * 4), L::acc_get(acc[i][j], rq * 4 + 1), L::acc_get(acc[i][j], rq * 4 + 2),
                      L::acc_get(acc[i][j], rq * 4 + 3)};
-          float* ap = accbuf + (int64_t)(n - a.acc_row0) * d + m;
+          float* ap = arow + c;
           if (flags & READ_ACC) v += *reinterpret_cast<const f32x4*>(ap);
           if (flags & WRITE_ACC) *reinterpret_cast<f32x4*>(ap) = v;
           if (flags & WRITE_OUT) {
             // "+ 0.f" turns a -0 product into +0
-            Pack4<T>::store(out + orow[j] * d + m, v[0] * scale + 0.f, v[1] * scale + 0.f, v[2] * scale + 0.f,
+            Pack4<T>::store(orowp + c, v[0] * scale + 0.f, v[1] * scale + 0.f, v[2] * scale + 0.f,
                             v[3] * scale + 0.f);
           }
           if (rq == 3) __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
