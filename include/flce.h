@@ -23,9 +23,15 @@
  *     error: the row is treated as ignored and FLCE_ERR_TARGET_RANGE is latched
  *     in the workspace (read it with flce_last_device_status).
  *   - The library never allocates device memory.  Scratch comes from the
- *     caller's `workspace` (size from flce_workspace_bytes; 256-byte aligned);
- *     it holds no N x V term.  The workspace contents are undefined on entry
- *     and between calls; forward and backward may use the same buffer.
+ *     caller's `workspace` (size from flce_workspace_bytes; 256-byte aligned).
+ *     The forward's is O(N + d) words plus one transposed copy of H; the
+ *     backward's is copies of H, fp32 running sums of the outputs where a
+ *     launch is chunked, and ONE staging tile for G of a capped size (see
+ *     flce_workspace_bytes): a problem smaller than the cap stages its whole
+ *     G there (in the storage type, half the bytes of fp32 logits for bf16),
+ *     a larger one never more than the cap.  The workspace contents are
+ *     undefined on entry and between calls; forward and backward may use
+ *     the same buffer.
  *   - All work is enqueued on `hip_stream` (a hipStream_t, NULL = the default
  *     stream) and the calls return without synchronising.  Outputs are fully
  *     overwritten.  Results are bit-identical from run to run for the same
@@ -97,8 +103,19 @@ const char* flce_status_string(flce_status s);
 /*
  * Bytes of device workspace needed by flce_forward (for_backward == 0) or
  * flce_backward (for_backward != 0) at this shape.  Returns 0 for an invalid
- * shape or dtype.  Grows like c1*(N+V)*d + c2*N + c3 with fixed-size staging
- * buffers: there is no N*V term.  Host call, touches no device.
+ * shape or dtype.  Host call, touches no device.
+ *   forward : 12 * windows * Npad + 4 * ceil(V/1024) * d + 4 * N + O(N/256) bytes, plus Npad * d elements for the
+ *             transposed copy of H (tuned bf16 loop).  Npad = N rounded up to 256.
+ *   backward: 2 * Npad * d elements (packed counted rows of H and their transpose) + 16 * Npad bytes
+ *             + the staging tile for G: Nc x (Vc + 64) elements with Nc = min(Npad, 32768) and
+ *               Vc = min(Vpad, 256 * vc) where vc = 128 tiles, or up to 512 when Nc < 8192 rows (so that
+ *               Nc * Vc stays within 2^25 elements there): at most 2 GiB + 4 MiB in bf16 whatever N and V,
+ *               512 MiB at N = 8192; below the cap this IS Npad x Vpad, the whole G in the storage type;
+ *             + fp32 running sums N * d (more than one vocabulary chunk) and Vc * d (more than one row chunk)
+ *             + fp32 K-slice tiles when a contraction launch is split (small N or small d);
+ *             the generic loop (fp32, or bf16 with d % 32 != 0) adds transposed copies of a W chunk and of G.
+ *   Beyond the cap the size grows like c1 * (N + V) * d + c2 * N + c3: no N * V term.  flce_plan_describe
+ *   prints the staging bytes of a shape.
  */
 size_t flce_workspace_bytes(int64_t N, int64_t d, int64_t V, flce_dtype dt, int for_backward);
 

@@ -29,7 +29,12 @@ def test_library_exports_every_declared_symbol():
     assert "target" in B.flce_status_string(B.FLCE_ERR_TARGET_RANGE)
 
 
-def test_workspace_has_no_NV_term():
+def plan_fields(N, d, V, dt):
+    text = B.flce_plan_describe(N, d, V, dt)
+    return text, {k: v for k, v in (t.split("=") for t in text.split() if "=" in t)}
+
+
+def test_workspace_beyond_the_staging_cap_has_no_NV_term():
     for dt in (B.FLCE_DTYPE_BF16, B.FLCE_DTYPE_F32):
         for bwd in (0, 1):
             base = B.flce_workspace_bytes(8192, 4096, 128256, dt, bwd)
@@ -42,6 +47,58 @@ def test_workspace_has_no_NV_term():
     assert ws < 0.12 * 131072 * 128256 * 4
     fw = B.flce_workspace_bytes(131072, 4096, 128256, B.FLCE_DTYPE_BF16, 0)
     assert fw < 131072 * 4096 * 2 + 64 * (1 << 20)          # at most one copy of H plus per-row partials
+    # staging never exceeds its cap however large the problem
+    for N, V in ((131072, 128256), (1 << 20, 1 << 20), (600000, 600), (600, 600000)):
+        _, f = plan_fields(N, 4096, V, B.FLCE_DTYPE_BF16)
+        assert int(f["staging_bytes"]) <= 32768 * (32768 + 64) * 2
+
+
+def test_workspace_below_the_staging_cap_is_what_the_header_says():
+    """A problem smaller than the staging cap stages its whole G (storage type): that part does grow like N x V,
+    everything else like (N + V) d.  Checked at a shape under the cap, at the same shape doubled, and at the tiny
+    fp32 benchmark shape (generic loop: transposed copies on top)."""
+    dt, e = B.FLCE_DTYPE_BF16, 2
+
+    def parts(N, d, V):
+        _, f = plan_fields(N, d, V, dt)
+        staging, total = int(f["staging_bytes"]), int(f["bwd_ws"])
+        assert total == B.flce_workspace_bytes(N, d, V, dt, 1)
+        return staging, total - staging
+
+    s1, r1 = parts(4096, 768, 16384)
+    s2, r2 = parts(8192, 768, 32768)
+    assert s1 == 4096 * (16384 + 64) * e and s2 == 8192 * (32768 + 64) * e      # the whole (padded) G
+    assert 3.9 < s2 / s1 < 4.1                                                    # that part is N x V
+    # the rest is (N + V) d: copies of H, fp32 running sums, at most 8 fp32 K-slice tiles of the larger output
+    for (N, d, V), rest in (((4096, 768, 16384), r1), ((8192, 768, 32768), r2)):
+        assert rest <= 2 * N * d * e + 16 * N + 4 * N * d + 4 * V * d + 8 * 4 * max(N, V) * d + (1 << 20)
+    # the bf16 staging is half the fp32 logits it replaces; with the other buffers the backward stays below them
+    assert B.flce_workspace_bytes(4096, 768, 50257, dt, 1) < 0.62 * 4096 * 50257 * 4
+    # tiny fp32 shape (generic loop): G, its transpose, a transposed W chunk and 8 K-slice tiles of dH
+    text, f = plan_fields(256, 256, 4096, B.FLCE_DTYPE_F32)
+    assert "loop=generic" in text
+    tiny = int(f["bwd_ws"])
+    assert tiny <= 4 * 256 * (4096 + 64) * 4 and tiny > 256 * 4096 * 4            # several times the 4 MB of logits
+    assert int(f["fwd_ws"]) < 64 * 1024
+
+
+def test_static_scratch_limit_is_checked_on_the_host():
+    p = 4096
+    assert B.flce_forward_static(p, p, p, 400000, 4096, 128256, -100, B.FLCE_REDUCE_MEAN, B.FLCE_DTYPE_BF16, p, p) == \
+        B.FLCE_ERR_WORKSPACE
+    assert B.flce_forward_static(None, p, p, 256, 64, 512, -100, B.FLCE_REDUCE_MEAN, B.FLCE_DTYPE_BF16, p, p) == \
+        B.FLCE_ERR_BAD_ARG
+
+
+def test_probe_and_plan_reject_bad_shapes_on_the_host():
+    p = 4096
+    assert B.flce_probe(0, p, p, p, 256, 256, 31, 4, 1, p) == B.FLCE_ERR_BAD_SHAPE       # K not a multiple of 32
+    assert B.flce_probe(0, p, p, p, 250, 256, 64, 4, 1, p) == B.FLCE_ERR_BAD_SHAPE       # rows not whole tiles
+    assert B.flce_probe(9, p, p, p, 256, 256, 64, 4, 1, p) == B.FLCE_ERR_BAD_ARG         # unknown mode
+    assert B.flce_probe(0, None, p, p, 256, 256, 64, 4, 1, p) == B.FLCE_ERR_BAD_ARG
+    with pytest.raises(ValueError):
+        B.flce_plan_describe(64, 60, 64, B.FLCE_DTYPE_BF16)
+    assert "windows=" in B.flce_plan_describe(64, 64, 64, B.FLCE_DTYPE_BF16)
 
 
 @pytest.mark.parametrize("N,d,V", [(0, 64, 64), (64, 0, 64), (64, 64, 0), (64, 60, 64), (-1, 64, 64)])

@@ -158,6 +158,37 @@ def test_streaming_per_position_gamma_matches_row_scaling():
     np.testing.assert_allclose(dW, G.T @ H, atol=1e-15)
 
 
+def test_streaming_pair_means_max_and_shifted_sum_on_every_prefix_and_split():
+    """The pair (m, a) the streaming forward carries IS (max, sum exp(z - max)) of what it has seen: after every
+    prefix of the vocabulary, for any cut of a range in two, in either order of combination, and with empty
+    parts; large logits (|z| ~ 300) so that a missing max shift would overflow."""
+    r = np.random.default_rng(77)
+    d, V = 5, 23
+    h = r.standard_normal(d) * 40.0
+    W = r.standard_normal((V, d)) * 3.0
+    z = W @ h
+    assert np.abs(z).max() > 200
+    for end in range(1, V + 1):
+        m, a, _, _ = S.stream_row(h, W, -1, 0, end)
+        assert m == z[:end].max()
+        assert abs(a - np.exp(z[:end] - z[:end].max()).sum()) <= 1e-12 * a
+    for lo, cut, hi in [(0, 7, 23), (3, 3, 19), (0, 22, 23), (5, 23, 23), (0, 0, 23)]:
+        left = S.stream_row(h, W, -1, lo, cut)[:2]
+        right = S.stream_row(h, W, -1, cut, hi)[:2]
+        whole = S.stream_row(h, W, -1, lo, hi)[:2]
+        for got in (S.combine(left, right), S.combine(right, left)):
+            assert got[0] == whole[0] and abs(got[1] - whole[1]) <= 1e-12 * whole[1]
+    assert S.combine(S.NOTHING, S.NOTHING) == S.NOTHING
+    # associativity on summaries of three ranges
+    a1, a2, a3 = (S.stream_row(h, W, -1, lo, hi)[:2] for lo, hi in ((0, 4), (4, 15), (15, 23)))
+    x, y_ = S.combine(S.combine(a1, a2), a3), S.combine(a1, S.combine(a2, a3))
+    assert x[0] == y_[0] and abs(x[1] - y_[1]) <= 1e-12 * x[1]
+    # the printed closing steps agree with m + log a - z_t where they are finite, and overflow where they are not
+    assert abs(S.closing_steps_as_printed(2.5, 3.0, 1.25) - (2.5 + np.log(3.0) - 1.25)) < 1e-14
+    with pytest.raises(OverflowError):
+        S.closing_steps_as_printed(800.0, 2.0, 1.0)
+
+
 @pytest.mark.parametrize("cuts", [[0, 13], [0, 4, 13], [0, 1, 2, 12, 13], [0, 0, 5, 5, 13]])
 def test_window_merge_equals_single_pass(cuts):
     N, d, V = 4, 6, 13
