@@ -683,8 +683,10 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
       // Tuned loop.  A lane holds, of 32 token rows x 128 vocabulary positions per j, scattered 8-byte pieces of one
       // row; stored as they lie, every store instruction would touch 64 different memory rows.  Each wavefront
       // therefore passes its 32 x 128 piece (8 KiB of bf16) through its own slice of the free LDS stage and writes
-      // whole 256-byte runs: 16 lanes per row, 4 rows per instruction.  LDS row = 256 bytes, its 16-byte chunks
-      // XOR-ed with the row number so that neither the 8-byte writes nor the 16-byte reads collide on banks.
+      // whole 256-byte runs: 16 lanes per row, 4 rows per instruction.  LDS row = 256 bytes = 32 slots of 8 bytes,
+      // slot index XOR-ed with the row number: the 32 rows that one 8-byte write instruction touches land in 32
+      // different slots (all 64 banks once), and a 16-byte read finds its two slots side by side, in swapped order
+      // on odd rows.
       static_assert(sizeof(T) == 2 && L::WM == 4 && L::WN == 4, "tuned epilogue is laid out for bf16 128 x 128 wave tiles");
       const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
       char* stage = lds + L::FREE_LDS_OFFSET + wave * 8192;
@@ -730,8 +732,8 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
             uint2 packed;
             packed.x = f32x2_to_bf16x2_bits(g[0], g[1]);
             packed.y = f32x2_to_bf16x2_bits(g[2], g[3]);
-            const int chunk = (i * 4 + rq) ^ (wrow & 15);
-            *reinterpret_cast<uint2*>(stage + wrow * 256 + chunk * 16 + whalf * 8) = packed;
+            const int slot = ((i * 4 + rq) * 2 + whalf) ^ wrow;
+            *reinterpret_cast<uint2*>(stage + wrow * 256 + slot * 8) = packed;
           }
           __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
         }
@@ -741,7 +743,8 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           const int r = k * 4 + rrow;
-          const u32x4 vq = *reinterpret_cast<const u32x4*>(stage + r * 256 + ((rchunk ^ (r & 15)) * 16));
+          u32x4 vq = *reinterpret_cast<const u32x4*>(stage + r * 256 + ((rchunk ^ (r >> 1)) * 16));
+          if (rrow & 1) vq = u32x4{vq[2], vq[3], vq[0], vq[1]};      // r is odd exactly when rrow is
           *reinterpret_cast<u32x4*>(gdst + (int64_t)r * ldG) = vq;
         }
       }
