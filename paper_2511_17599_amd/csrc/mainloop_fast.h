@@ -40,10 +40,13 @@ namespace fast {
 constexpr int THREADS = 256;
 constexpr int WM = 4, WN = 4;
 constexpr int BK = 32;                    // K elements per stage
-constexpr int NS = 4;                     // stages
+#ifndef FLCE_STAGES
+#define FLCE_STAGES 4
+#endif
+constexpr int NS = FLCE_STAGES;           // stages
 constexpr int OPER = TILE * BK * 2;       // 16 KiB per operand per stage (either layout)
 constexpr int STAGE = 2 * OPER;
-constexpr int LDS_BYTES = NS * STAGE;     // 128 KiB
+constexpr int LDS_BYTES = NS * STAGE;     // 128 KiB with 4 stages
 constexpr int LOADS_PER_TILE = 8;         // buffer_load...lds instructions per wavefront per stage
 
 enum : int { KC = 0, KR = 1 };
@@ -237,6 +240,18 @@ struct Pipe {
       }
   }
 
+  // waits until at most n whole K tiles of this wavefront's requests are outstanding (and its LDS reads returned)
+  static __device__ __forceinline__ void wait_tiles_in_flight(int n) {
+    static_assert(NS >= 3 && NS <= 6, "the switch below covers up to NS - 2 tiles in flight");
+    switch (n) {
+      case 0: wait_vm_and_lds<0>(); break;
+      case 1: wait_vm_and_lds<LOADS_PER_TILE>(); break;
+      case 2: wait_vm_and_lds<2 * LOADS_PER_TILE>(); break;
+      case 3: wait_vm_and_lds<3 * LOADS_PER_TILE>(); break;
+      default: wait_vm_and_lds<4 * LOADS_PER_TILE>(); break;
+    }
+  }
+
   __device__ __forceinline__ void run(char* lds, f32x16 (&acc)[WM][WN]) {
     constexpr int RA = FragAddr<LA>::READS, RB = FragAddr<LB>::READS, RT = RA + RB;
     if (KT <= 0) {          // an empty K extent (no counted row, or a K slice past the end): the tile is zero
@@ -250,10 +265,8 @@ struct Pipe {
       return;
     }
 
-    // tile 0 has landed once at most tiles 1 and 2 are in flight
-    if (KT > 2) wait_vm_and_lds<2 * LOADS_PER_TILE>();
-    else if (KT > 1) wait_vm_and_lds<LOADS_PER_TILE>();
-    else wait_vm_and_lds<0>();
+    // tile 0 has landed once only the other tiles requested by start() are in flight
+    wait_tiles_in_flight(min(KT, NS - 1) - 1);
     __builtin_amdgcn_s_barrier();
     Frags f0, f1;
 #pragma unroll
@@ -300,37 +313,35 @@ struct Pipe {
     constexpr std::true_type FIRST{};
     constexpr std::false_type LATER{};
 
-    // Steady state: K step kt computes tile kt and requests tile kt+3 into the stage that
-    // was freed by the barrier of step kt-1.
-    auto steady_step = [&](auto first, int kt) {
-      const char* cur = lds + (kt & (NS - 1)) * STAGE;
-      const char* nxt = lds + ((kt + 1) & (NS - 1)) * STAGE;
-      char* lst = lds + ((kt + NS - 1) & (NS - 1)) * STAGE;
-      half_step(first, f0, f1, cur, 1, 0, kt + NS - 1, lst);
-      // tile kt+1 has landed once only tile kt+2 and the first half of tile kt+3 are in flight;
+    // Steady state: K step kt computes tile kt (stage sc) and requests tile kt+NS-1 into the stage that
+    // was freed by the barrier of step kt-1 (the one before sc in the ring).
+    auto stage_at = [&](int idx) { return lds + idx * STAGE; };
+    auto after = [](int idx) { return idx + 1 == NS ? 0 : idx + 1; };
+    auto before = [](int idx) { return idx == 0 ? NS - 1 : idx - 1; };
+    auto steady_step = [&](auto first, int kt, int sc) {
+      char* lst = stage_at(before(sc));
+      half_step(first, f0, f1, stage_at(sc), 1, 0, kt + NS - 1, lst);
+      // tile kt+1 has landed once only tiles kt+2 .. kt+NS-2 and the first half of tile kt+NS-1 are in flight;
       // lgkmcnt(0): this wavefront holds all its fragments of tile kt
-      wait_vm_and_lds<LOADS_PER_TILE + LOADS_PER_TILE / 2>();
+      wait_vm_and_lds<(NS - 3) * LOADS_PER_TILE + LOADS_PER_TILE / 2>();
       __builtin_amdgcn_s_barrier();
-      half_step(LATER, f1, f0, nxt, 0, 1, kt + NS - 1, lst);
+      half_step(LATER, f1, f0, stage_at(after(sc)), 0, 1, kt + NS - 1, lst);
     };
     // Drain: the last (up to NS-1) tiles, nothing left to request.
-    auto drain_step = [&](auto first, int kt) {
-      const char* cur = lds + (kt & (NS - 1)) * STAGE;
-      const char* nxt = lds + ((kt + 1) & (NS - 1)) * STAGE;   // past the last tile: stale data, never used
-      half_step(first, f0, f1, cur, 1, 0, -1, nullptr);
-      if (kt + 2 < KT) wait_vm_and_lds<LOADS_PER_TILE>();
-      else wait_vm_and_lds<0>();
+    auto drain_step = [&](auto first, int kt, int sc) {
+      half_step(first, f0, f1, stage_at(sc), 1, 0, -1, nullptr);
+      wait_tiles_in_flight(max(0, KT - kt - 2));            // tile kt+1 landed; the later ones may be in flight
       __builtin_amdgcn_s_barrier();
-      half_step(LATER, f1, f0, nxt, 0, 1, -1, nullptr);
+      half_step(LATER, f1, f0, stage_at(after(sc)), 0, 1, -1, nullptr);   // past the last tile: stale data, never used
     };
-    int kt = 1;
+    int kt = 1, sc = 1 % NS;
     if (NS - 1 < KT) {
-      steady_step(FIRST, 0);
-      for (; kt + NS - 1 < KT; ++kt) steady_step(LATER, kt);
+      steady_step(FIRST, 0, 0);
+      for (; kt + NS - 1 < KT; ++kt, sc = after(sc)) steady_step(LATER, kt, sc);
     } else {
-      drain_step(FIRST, 0);
+      drain_step(FIRST, 0, 0);
     }
-    for (; kt < KT; ++kt) drain_step(LATER, kt);
+    for (; kt < KT; ++kt, sc = after(sc)) drain_step(LATER, kt, sc);
     wait_vm_and_lds<0>();
     __builtin_amdgcn_s_barrier();
   }
