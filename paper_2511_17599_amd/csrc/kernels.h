@@ -122,6 +122,9 @@ struct FastLoop {         // bf16, K a multiple of 32 elements; 4 wavefronts 2 x
   }
 };
 
+#ifndef FLCE_FWD_GROUP
+#define FLCE_FWD_GROUP 8     // row blocks per raster patch of the forward (x 32 / this many windows per XCD)
+#endif
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float NEG_INF = -__builtin_inff();
 
@@ -212,7 +215,7 @@ __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
   extern __shared__ __align__(16) char lds[];
   const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
   int rb, win;
-  grouped_raster(id, n_rb, n_win, 8, rb, win);
+  grouped_raster(id, n_rb, n_win, FLCE_FWD_GROUP, rb, win);
   const int vt_begin = (int)((int64_t)win * n_vt / n_win);
   const int vt_end = (int)((int64_t)(win + 1) * n_vt / n_win);
   const int n0 = rb * TILE;
