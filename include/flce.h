@@ -331,6 +331,8 @@ flce_status flce_profile_collect(double* ms_by_class, int64_t* launches_by_class
  *   mode 2 : the complete main loop, both operands K-contiguous
  *   mode 3, 4 : modes 1, 2 with the matrix instructions left out (global -> LDS requests, LDS reads, waits and
  *            barriers only): the data path alone
+ *   mode 5 : mode 0's MFMAs and mode 1's requests and LDS reads issued side by side with no wait or barrier between
+ *            them (what is read is discarded): the two streams when neither waits for the other
  *   A  : device, bf16 [a_rows][k_elems];  B : device, bf16 [b_rows][k_elems];  BT : device, bf16 [k_elems][b_rows]
  *        (a_rows, b_rows multiples of 256, k_elems a multiple of 32); contents are the caller's choice of data.
  *   sink : device, workgroups * 256 floats, written once per thread.

@@ -823,6 +823,7 @@ flce_status flce_probe(int mode, const void* A, const void* B, const void* BT, i
     case flce::PROBE_LOOP_KC: return launch(flce::probe_kernel<flce::PROBE_LOOP_KC>);
     case flce::PROBE_DATA_KR: return launch(flce::probe_kernel<flce::PROBE_DATA_KR>);
     case flce::PROBE_DATA_KC: return launch(flce::probe_kernel<flce::PROBE_DATA_KC>);
+    case flce::PROBE_FREE_RUN: return launch(flce::probe_kernel<flce::PROBE_FREE_RUN>);
   }
   return FLCE_ERR_BAD_ARG;
 }

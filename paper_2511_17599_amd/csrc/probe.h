@@ -8,12 +8,16 @@
 //   PROBE_LOOP_KC  : the same with both operands K-contiguous.
 //   PROBE_DATA_KR / PROBE_DATA_KC : those loops with the matrix instructions left out (global -> LDS requests, LDS
 //                    fragment reads, waits, barriers only): the data path alone.
+//   PROBE_FREE_RUN : the matrix instructions from registers AND the forward layout's global -> LDS requests and LDS
+//                    fragment reads of every K step, issued side by side with no wait or barrier between them (the
+//                    fragments read are discarded): what the two streams reach when nothing makes one wait for the
+//                    other, i.e. how much of the complete loop's loss is synchronisation.
 #pragma once
 #include "mainloop_fast.h"
 
 namespace flce {
 
-enum : int { PROBE_MFMA = 0, PROBE_LOOP_KR = 1, PROBE_LOOP_KC = 2, PROBE_DATA_KR = 3, PROBE_DATA_KC = 4 };
+enum : int { PROBE_MFMA = 0, PROBE_LOOP_KR = 1, PROBE_LOOP_KC = 2, PROBE_DATA_KR = 3, PROBE_DATA_KC = 4, PROBE_FREE_RUN = 5 };
 
 struct ProbeArgs {
   const bf16_t* A;      // [a_rows][k_elems], K-contiguous (plays W)
@@ -55,6 +59,64 @@ __global__ __launch_bounds__(fast::THREADS) void probe_kernel(ProbeArgs p) {
         for (int j = 0; j < fast::WN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
+  } else if constexpr (MODE == PROBE_FREE_RUN) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    bf16x8 fa[fast::WM], fb[fast::WN];
+#pragma unroll
+    for (int i = 0; i < fast::WM; ++i)
+      fa[i] = *reinterpret_cast<const bf16x8*>(p.A + (int64_t)((wave * 4 + i) * 64 + lane) % p.a_rows * p.k_elems);
+#pragma unroll
+    for (int j = 0; j < fast::WN; ++j)
+      fb[j] = *reinterpret_cast<const bf16x8*>(p.B + (int64_t)(b0 + (wave * 4 + j) * 64 % TILE + lane) % p.b_rows * p.k_elems);
+#pragma unroll
+    for (int i = 0; i < fast::WM; ++i)
+#pragma unroll
+      for (int j = 0; j < fast::WN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    fast::Loader<fast::KC> la;
+    fast::Loader<fast::KR> lb;
+    fast::FragAddr<fast::KC> fra;
+    fast::FragAddr<fast::KR> frb;
+    fra.init(wave >> 1);
+    frb.init(wave & 1);
+    const int lds_wave = __builtin_amdgcn_readfirstlane(wave) * 4096;
+    const int64_t ld = (int64_t)p.k_elems * 2;
+    const int KT = p.k_elems / fast::BK;
+    for (int t = 0; t < p.tiles_per_wg; ++t) {
+      const int a0 = ((blockIdx.x / n_bt + t) % n_at) * TILE;
+      const fast::Operand As{reinterpret_cast<const char*>(p.A), ld, a0, p.a_rows, 0};
+      const fast::Operand Bs{reinterpret_cast<const char*>(p.BT) + (int64_t)b0 * 2, (int64_t)p.b_rows * 2, 0, p.k_elems,
+                             TILE * 2};
+      la.init(As, p.k_elems);
+      lb.init(Bs, p.k_elems);
+      for (int kt = 0; kt < KT; ++kt) {
+        char* st = lds + (kt & (fast::NS - 1)) * fast::STAGE;
+        fast::Frags junk;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+          for (int s16 = 0; s16 < 16; ++s16) {
+            const int mi = s16 >> 2, mj = s16 & 3;
+            acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[mj], acc[mi][mj], 0, 0, 0);
+            // the forward layout's 12 fragment reads per half step, results never waited for
+            if (s16 < 12) {
+              if (s16 < 4) fast::read_frag<fast::KC>(junk.a, fra, st, h, s16);
+              else fast::read_frag<fast::KR>(junk.b, frb, st + fast::OPER, h, s16 - 4);
+            }
+            if ((s16 & 3) == 2) {
+              if (h == 0) la.issue(s16 >> 2, st + lds_wave, kt);
+              else lb.issue(s16 >> 2, st + fast::OPER + lds_wave, kt);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+        asm volatile("" ::"v"(junk.a[0]), "v"(junk.a[1]), "v"(junk.a[2]), "v"(junk.a[3]), "v"(junk.b[0]), "v"(junk.b[1]),
+                     "v"(junk.b[2]), "v"(junk.b[3]));
+      }
+    }
+    fast::wait_vm_and_lds<0>();
+    __builtin_amdgcn_s_barrier();
   } else {
     constexpr int LB = (MODE == PROBE_LOOP_KR || MODE == PROBE_DATA_KR) ? fast::KR : fast::KC;
     constexpr bool MF = MODE == PROBE_LOOP_KR || MODE == PROBE_LOOP_KC;
@@ -84,7 +146,7 @@ __global__ __launch_bounds__(fast::THREADS) void probe_kernel(ProbeArgs p) {
       }
     }
   }
-  if constexpr (MODE == PROBE_MFMA) {
+  if constexpr (MODE == PROBE_MFMA || MODE == PROBE_FREE_RUN) {
     // one element of every accumulator block keeps every MFMA chain alive
 #pragma unroll
     for (int i = 0; i < fast::WM; ++i)
