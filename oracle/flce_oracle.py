@@ -21,8 +21,7 @@ with Gamma = grad_loss / n_valid for the mean and grad_loss for the sum (the
 purpose.  All arithmetic is IEEE fp64; numpy's matmul is the only library
 primitive used as a step.
 
-Readings taken where the paper is silent (each is also listed in the design
-document):
+Readings taken where the paper is silent:
   * targets are 0-based, in [0, V) (the paper writes {1..V});
   * rows whose target equals ``ignore_index`` contribute loss 0, a zero row of
     G, and are left out of the mean's denominator;
