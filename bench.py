@@ -172,14 +172,16 @@ def probe_main_loop(steps, warmup):
         A = (torch.randn(a_rows, k, device="cuda", generator=g) * 0.02).to(torch.bfloat16)
         Bm = torch.randn(b_rows, k, device="cuda", generator=g).to(torch.bfloat16)
         BT = Bm.t().contiguous()
-        sink = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+        sink = torch.empty(2 * wgs * 256, dtype=torch.float32, device="cuda")
         st = torch.cuda.current_stream()
         for mode, name in enumerate(B.PROBE_MODES):
             ms = []
+            # the half-height-tile modes: twice the workgroups (two per CU) for the same total work
+            launch_wgs = 2 * wgs if name.startswith("half") else wgs
             for it in range(warmup + steps):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(st)
-                rc = B.flce_probe(mode, A, Bm, BT, a_rows, b_rows, k, wgs, tiles, sink, st)
+                rc = B.flce_probe(mode, A, Bm, BT, a_rows, b_rows, k, launch_wgs, tiles, sink, st)
                 e1.record(st)
                 assert rc == B.FLCE_OK, B.flce_status_string(rc)
                 e1.synchronize()
@@ -189,7 +191,7 @@ def probe_main_loop(steps, warmup):
             med = ms[len(ms) // 2]
             flops = 2.0 * 256 * 256 * k * tiles * wgs
             lds_bytes = 2.0 * 256 * k * 2 * tiles * wgs                # operand bytes brought into LDS
-            line = {"probe": name, "k_elems": k, "workgroups": wgs, "tiles_per_workgroup": tiles,
+            line = {"probe": name, "k_elems": k, "workgroups": launch_wgs, "tiles_per_workgroup": tiles,
                     "ms_median": med, "ms_min": ms[0], "device": props.name, "compute_units": props.multi_processor_count}
             if name.startswith("data"):
                 line["global_to_lds_TBps"] = lds_bytes / (med * 1e-3) / 1e12

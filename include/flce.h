@@ -333,6 +333,11 @@ flce_status flce_profile_collect(double* ms_by_class, int64_t* launches_by_class
  *            barriers only): the data path alone
  *   mode 5 : mode 0's MFMAs and mode 1's requests and LDS reads issued side by side with no wait or barrier between
  *            them (what is read is discarded): the two streams when neither waits for the other
+ *   mode 6 : mode 1 plus, after every tile, the plain-ALU work of the forward's tile post-processing (a maximum and
+ *            a sum of exponentials over the accumulators), done by the same wavefronts, nothing overlapped
+ *   mode 7, 8 : modes 1 and 6 on tiles of 128 x 256 outputs (128 accumulators per lane, three stages) so that two
+ *            workgroups share a CU and one's post-processing overlaps the other's matrix work; a tile is half
+ *            the work, so these modes execute half the flops stated below per workgroup
  *   A  : device, bf16 [a_rows][k_elems];  B : device, bf16 [b_rows][k_elems];  BT : device, bf16 [k_elems][b_rows]
  *        (a_rows, b_rows multiples of 256, k_elems a multiple of 32); contents are the caller's choice of data.
  *   sink : device, workgroups * 256 floats, written once per thread.

@@ -803,6 +803,7 @@ flce_status flce_last_device_status(const void* workspace, void* hip_stream, int
 flce_status flce_probe(int mode, const void* A, const void* B, const void* BT, int64_t a_rows, int64_t b_rows,
                        int64_t k_elems, int workgroups, int tiles_per_workgroup, float* sink, void* hip_stream) {
   if (!A || !B || !BT || !sink) return FLCE_ERR_BAD_ARG;
+  if (mode < flce::PROBE_MFMA || mode > flce::PROBE_HALF_KR_SOFTMAX) return FLCE_ERR_BAD_ARG;
   if (a_rows <= 0 || b_rows <= 0 || (a_rows % flce::TILE) || (b_rows % flce::TILE) || k_elems < 32 || (k_elems % 32) ||
       workgroups <= 0 || tiles_per_workgroup <= 0)
     return FLCE_ERR_BAD_SHAPE;
@@ -812,9 +813,9 @@ flce_status flce_probe(int mode, const void* A, const void* B, const void* BT, i
   const flce::ProbeArgs pa{static_cast<const flce::bf16_t*>(A), static_cast<const flce::bf16_t*>(B),
                            static_cast<const flce::bf16_t*>(BT), (int)a_rows, (int)b_rows, (int)k_elems,
                            tiles_per_workgroup, sink};
-  auto launch = [&](auto kernel) -> flce_status {
-    if (flce::allow_big_lds(kernel, flce::fast::LDS_BYTES) != hipSuccess) return FLCE_ERR_HIP;
-    kernel<<<workgroups, flce::fast::THREADS, flce::fast::LDS_BYTES, st>>>(pa);
+  auto launch = [&](auto kernel, int lds_bytes = flce::fast::LDS_BYTES) -> flce_status {
+    if (flce::allow_big_lds(kernel, lds_bytes) != hipSuccess) return FLCE_ERR_HIP;
+    kernel<<<workgroups, flce::fast::THREADS, lds_bytes, st>>>(pa);
     return hipGetLastError() == hipSuccess ? FLCE_OK : FLCE_ERR_HIP;
   };
   switch (mode) {
@@ -824,6 +825,9 @@ flce_status flce_probe(int mode, const void* A, const void* B, const void* BT, i
     case flce::PROBE_DATA_KR: return launch(flce::probe_kernel<flce::PROBE_DATA_KR>);
     case flce::PROBE_DATA_KC: return launch(flce::probe_kernel<flce::PROBE_DATA_KC>);
     case flce::PROBE_FREE_RUN: return launch(flce::probe_kernel<flce::PROBE_FREE_RUN>);
+    case flce::PROBE_LOOP_KR_SOFTMAX: return launch(flce::probe_kernel<flce::PROBE_LOOP_KR_SOFTMAX>);
+    case flce::PROBE_HALF_KR: return launch(flce::probe_half_kernel<false>, flce::PROBE_HALF_LDS);
+    case flce::PROBE_HALF_KR_SOFTMAX: return launch(flce::probe_half_kernel<true>, flce::PROBE_HALF_LDS);
   }
   return FLCE_ERR_BAD_ARG;
 }

@@ -47,7 +47,6 @@ constexpr int NS = FLCE_STAGES;           // stages
 constexpr int OPER = TILE * BK * 2;       // 16 KiB per operand per stage (either layout)
 constexpr int STAGE = 2 * OPER;
 constexpr int LDS_BYTES = NS * STAGE;     // 128 KiB with 4 stages
-constexpr int LOADS_PER_TILE = 8;         // buffer_load...lds instructions per wavefront per stage
 
 enum : int { KC = 0, KR = 1 };
 
@@ -85,12 +84,12 @@ __device__ __forceinline__ uint32_t lds_address(const char* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
 }
 
-template <int LAYOUT>
+template <int LAYOUT, int TILE_ROWS = TILE>
 __device__ __forceinline__ u32x4 make_rsrc(const Operand& s, int k_elems) {
   uint32_t n = 0;
   const char* b = s.base;
   if (LAYOUT == KC) {
-    int vr = min(TILE, s.rows - s.row0);
+    int vr = min(TILE_ROWS, s.rows - s.row0);
     if (vr > 0) n = (uint32_t)((int64_t)(vr - 1) * s.ld_bytes + k_elems * 2);
     b += (int64_t)s.row0 * s.ld_bytes;
   } else {
@@ -127,20 +126,21 @@ __device__ __forceinline__ void wait_vm_and_lds() {
   __builtin_amdgcn_s_waitcnt((hi << 14) | (0x0 << 8) | (0x7 << 4) | lo);
 }
 
-// Global -> LDS requests of one operand: 4 per wavefront per stage, 1 KiB each, written
-// linearly into this wavefront's 4 KiB slice of the operand tile.
-template <int LAYOUT>
+// Global -> LDS requests of one operand: REQS per wavefront per stage (4 for a 256-row tile; a K-contiguous tile
+// may also be 128 rows high: 2), 1 KiB each, written linearly into this wavefront's slice of the operand tile.
+template <int LAYOUT, int REQS = 4>
 struct Loader {
+  static_assert(REQS == 4 || (LAYOUT == KC && REQS == 2), "a half-height tile exists in the K-contiguous layout only");
   u32x4 rs;
-  uint32_t v[4];          // per-lane byte offsets of the 4 requests (K tile 0); unsigned: a window may reach 2^32 bytes
+  uint32_t v[REQS];       // per-lane byte offsets of the requests (K tile 0); unsigned: a window may reach 2^32 bytes
   uint32_t k_step;        // KC: bytes of K per stage (scalar offset); KR: bytes of 32 K rows (added per lane)
   __device__ __forceinline__ void init(const Operand& s, int k_elems) {
-    rs = make_rsrc<LAYOUT>(s, k_elems);
+    rs = make_rsrc<LAYOUT, 64 * REQS>(s, k_elems);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < REQS; ++i) {
       if (LAYOUT == KC) {
-        const int row = wave * 64 + i * 16 + (lane >> 2);
+        const int row = wave * (16 * REQS) + i * 16 + (lane >> 2);
         const int chunk = (lane & 3) ^ ((row >> 2) & 3);
         v[i] = (uint32_t)(row * s.ld_bytes) + chunk * 16;
       } else {
@@ -160,17 +160,18 @@ struct Loader {
   }
 };
 
-// Per-lane LDS byte offsets of the fragment reads of one operand; wsub = which 128-row
-// half of the tile this wavefront works on.
-template <int LAYOUT>
+// Per-lane LDS byte offsets of the fragment reads of one operand; wsub = which half of the tile's rows this
+// wavefront works on (BLOCKS 32-row blocks each: 4 for a 256-row tile, 2 for a 128-row one).
+template <int LAYOUT, int BLOCKS = 4>
 struct FragAddr {
+  static_assert(BLOCKS == 4 || (LAYOUT == KC && BLOCKS == 2), "a half-height tile exists in the K-contiguous layout only");
   int o[4];   // KC: o[ks] for the two MFMA K steps (o[2], o[3] unused); KR: o[i] for the 4 blocks
   __device__ __forceinline__ void init(int wsub) {
     const int lane = threadIdx.x & 63;
     if (LAYOUT == KC) {
       const int l32 = lane & 31, half = lane >> 5, sw = (l32 >> 2) & 3;
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) o[ks] = (wsub * 128 + l32) * 64 + (((ks * 2 + half) ^ sw) << 4);
+      for (int ks = 0; ks < 2; ++ks) o[ks] = (wsub * 32 * BLOCKS + l32) * 64 + (((ks * 2 + half) ^ sw) << 4);
       o[2] = o[3] = 0;
     } else {
       const int e = (lane >> 2) & 3, q = lane & 3, mg = (lane >> 4) & 1, kh = lane >> 5;
@@ -178,7 +179,7 @@ struct FragAddr {
       for (int i = 0; i < 4; ++i) o[i] = (8 * kh + e) * 512 + wsub * 256 + 64 * (i ^ e) + 32 * mg + 8 * q;
     }
   }
-  static constexpr int READS = LAYOUT == KC ? 4 : 8;   // LDS reads per MFMA K step
+  static constexpr int READS = LAYOUT == KC ? BLOCKS : 8;   // LDS reads per MFMA K step
 };
 
 struct Frags {
@@ -186,8 +187,8 @@ struct Frags {
 };
 
 // Read number t (0 .. READS-1) of the fragments of one operand for MFMA K step ks of a stage.
-template <int LAYOUT>
-__device__ __forceinline__ void read_frag(bf16x8 (&f)[4], const FragAddr<LAYOUT>& fa, const char* tile, int ks, int t) {
+template <int LAYOUT, int BLOCKS>
+__device__ __forceinline__ void read_frag(bf16x8 (&f)[4], const FragAddr<LAYOUT, BLOCKS>& fa, const char* tile, int ks, int t) {
   if (LAYOUT == KC) {
     f[t] = *reinterpret_cast<const bf16x8*>(tile + fa.o[ks] + t * 32 * 64);
   } else {
@@ -210,11 +211,22 @@ __device__ __forceinline__ void read_frag(bf16x8 (&f)[4], const FragAddr<LAYOUT>
 //
 // WITH_MFMA = false leaves the matrix instructions out (everything else, i.e. the global -> LDS requests, the LDS
 // fragment reads, the waits and barriers, stays): only the measurement probe uses it, to time the data path alone.
-template <int LA, int LB, bool WITH_MFMA = true>
+//
+// AM = 32-row blocks of A per wavefront: 4 is the 256 x 256 tile above; 2 halves the A tile (128 rows, K-contiguous
+// only), i.e. a 128 x 256 tile with 128 accumulators per lane, which lets two workgroups share a CU (with NSTAGES = 3
+// a workgroup then needs 72 KiB of LDS).  `acc` has AM x 4 blocks.
+template <int LA, int LB, bool WITH_MFMA = true, int AM = WM, int NSTAGES = NS>
 struct Pipe {
-  Loader<LA> la;
+  static_assert(AM == 4 || (AM == 2 && LA == KC), "a half-height A tile exists in the K-contiguous layout only");
+  static constexpr int REQS_A = AM;                    // requests per wavefront per stage, A (1 KiB each)
+  static constexpr int OPER_A = AM * 4096;             // bytes of the A tile of one stage
+  static constexpr int STAGE_BYTES = OPER_A + OPER;    // A tile, then B tile
+  static constexpr int LDS_TOTAL = NSTAGES * STAGE_BYTES;
+  static constexpr int LOADS = REQS_A + 4;             // requests per wavefront per K tile
+  static constexpr int NM = AM * WN;                   // MFMAs per half step
+  Loader<LA, REQS_A> la;
   Loader<LB> lb;
-  FragAddr<LA> fa;
+  FragAddr<LA, AM> fa;
   FragAddr<LB> fb;
   int KT, lds_wave;
 
@@ -225,38 +237,38 @@ struct Pipe {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     fa.init(wave >> 1);
     fb.init(wave & 1);
-    lds_wave = wave * 4096;
+    lds_wave = wave * 4096;      // this wavefront's slice of a 256-row operand tile (of a shorter A tile: pro rata)
     // Opaque to the optimiser: in a kernel that walks several tiles these two are loop invariant, and everything
     // derived from them (a dozen comparisons of the K count, the LDS address of every request of every stage)
     // would be precomputed once and kept alive in scalar registers across the whole tile loop, which overflows them.
     asm volatile("" : "+s"(KT), "+s"(lds_wave));
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
+    for (int s = 0; s < NSTAGES - 1; ++s)
       if (s < KT) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) la.issue(i, lds + s * STAGE + lds_wave, s);
+        for (int i = 0; i < REQS_A; ++i) la.issue(i, lds + s * STAGE_BYTES + lds_wave * REQS_A / 4, s);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) lb.issue(i, lds + s * STAGE + OPER + lds_wave, s);
+        for (int i = 0; i < 4; ++i) lb.issue(i, lds + s * STAGE_BYTES + OPER_A + lds_wave, s);
       }
   }
 
   // waits until at most n whole K tiles of this wavefront's requests are outstanding (and its LDS reads returned)
   static __device__ __forceinline__ void wait_tiles_in_flight(int n) {
-    static_assert(NS >= 3 && NS <= 6, "the switch below covers up to NS - 2 tiles in flight");
+    static_assert(NSTAGES >= 3 && NSTAGES <= 6, "the switch below covers up to NSTAGES - 2 tiles in flight");
     switch (n) {
       case 0: wait_vm_and_lds<0>(); break;
-      case 1: wait_vm_and_lds<LOADS_PER_TILE>(); break;
-      case 2: wait_vm_and_lds<2 * LOADS_PER_TILE>(); break;
-      case 3: wait_vm_and_lds<3 * LOADS_PER_TILE>(); break;
-      default: wait_vm_and_lds<4 * LOADS_PER_TILE>(); break;
+      case 1: wait_vm_and_lds<LOADS>(); break;
+      case 2: wait_vm_and_lds<2 * LOADS>(); break;
+      case 3: wait_vm_and_lds<3 * LOADS>(); break;
+      default: wait_vm_and_lds<4 * LOADS>(); break;
     }
   }
 
-  __device__ __forceinline__ void run(char* lds, f32x16 (&acc)[WM][WN]) {
-    constexpr int RA = FragAddr<LA>::READS, RB = FragAddr<LB>::READS, RT = RA + RB;
+  __device__ __forceinline__ void run(char* lds, f32x16 (&acc)[AM][WN]) {
+    constexpr int RA = FragAddr<LA, AM>::READS, RB = FragAddr<LB>::READS, RT = RA + RB;
     if (KT <= 0) {          // an empty K extent (no counted row, or a K slice past the end): the tile is zero
 #pragma unroll
-      for (int i = 0; i < WM; ++i)
+      for (int i = 0; i < AM; ++i)
 #pragma unroll
         for (int j = 0; j < WN; ++j)
 #pragma unroll
@@ -266,16 +278,16 @@ struct Pipe {
     }
 
     // tile 0 has landed once only the other tiles requested by start() are in flight
-    wait_tiles_in_flight(min(KT, NS - 1) - 1);
+    wait_tiles_in_flight(min(KT, NSTAGES - 1) - 1);
     __builtin_amdgcn_s_barrier();
     Frags f0, f1;
 #pragma unroll
     for (int t = 0; t < RA; ++t) read_frag<LA>(f0.a, fa, lds, 0, t);
 #pragma unroll
-    for (int t = 0; t < RB; ++t) read_frag<LB>(f0.b, fb, lds + OPER, 0, t);
+    for (int t = 0; t < RB; ++t) read_frag<LB>(f0.b, fb, lds + OPER_A, 0, t);
 
-    // One half of a K step: the 16 MFMAs of fragment set FM; between them the LDS reads that
-    // fill fragment set FR (stage `st`, MFMA K step ks) and, if load_kt >= 0, the 4 global
+    // One half of a K step: the NM (16) MFMAs of fragment set FM; between them the LDS reads that
+    // fill fragment set FR (stage `st`, MFMA K step ks) and, if load_kt >= 0, the global
     // requests of operand `which` (0 = A, 1 = B) of K tile load_kt into stage `lst`.
     // `first`: the very first half step of a tile starts every accumulator block from zero (the
     // matrix instruction takes the constant as its addend: no pass over the 256 registers to clear them).
@@ -283,7 +295,7 @@ struct Pipe {
                          char* lst) {
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int s = 0; s < 16; ++s) {
+      for (int s = 0; s < NM; ++s) {
         const int mi = s >> 2, mj = s & 3;
         if constexpr (WITH_MFMA) {
           if constexpr (decltype(first)::value) {
@@ -296,16 +308,21 @@ struct Pipe {
           // keep the fragment reads alive without arithmetic on them
           asm volatile("" ::"v"(FM.a[mi]), "v"(FM.b[mj]));
         }
-        // reads t with t * 16 / RT == s: spread evenly over the 16 slots
+        // reads t with t * NM / RT == s: spread evenly over the MFMA slots
 #pragma unroll
         for (int t = 0; t < RT; ++t)
-          if (t * 16 / RT == s) {
+          if (t * NM / RT == s) {
             if (t < RA) read_frag<LA>(FR.a, fa, st, ks, t);
-            else read_frag<LB>(FR.b, fb, st + OPER, ks, t - RA);
+            else read_frag<LB>(FR.b, fb, st + OPER_A, ks, t - RA);
           }
-        if ((s & 3) == 2 && load_kt >= 0) {
-          if (which == 0) la.issue(s >> 2, lst + lds_wave, load_kt);
-          else lb.issue(s >> 2, lst + OPER + lds_wave, load_kt);
+        // the requests of one operand, evenly spread too: one in the middle of every NM / requests slots
+        constexpr int PER_A = NM / REQS_A, PER_B = NM / 4;
+        if (load_kt >= 0) {
+          if (which == 0) {
+            if (s % PER_A == PER_A / 2) la.issue(s / PER_A, lst + lds_wave * REQS_A / 4, load_kt);
+          } else {
+            if (s % PER_B == PER_B / 2) lb.issue(s / PER_B, lst + OPER_A + lds_wave, load_kt);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -313,19 +330,19 @@ struct Pipe {
     constexpr std::true_type FIRST{};
     constexpr std::false_type LATER{};
 
-    // Steady state: K step kt computes tile kt (stage sc) and requests tile kt+NS-1 into the stage that
+    // Steady state: K step kt computes tile kt (stage sc) and requests tile kt+NSTAGES-1 into the stage that
     // was freed by the barrier of step kt-1 (the one before sc in the ring).
-    auto stage_at = [&](int idx) { return lds + idx * STAGE; };
-    auto after = [](int idx) { return idx + 1 == NS ? 0 : idx + 1; };
-    auto before = [](int idx) { return idx == 0 ? NS - 1 : idx - 1; };
+    auto stage_at = [&](int idx) { return lds + idx * STAGE_BYTES; };
+    auto after = [](int idx) { return idx + 1 == NSTAGES ? 0 : idx + 1; };
+    auto before = [](int idx) { return idx == 0 ? NSTAGES - 1 : idx - 1; };
     auto steady_step = [&](auto first, int kt, int sc) {
       char* lst = stage_at(before(sc));
-      half_step(first, f0, f1, stage_at(sc), 1, 0, kt + NS - 1, lst);
-      // tile kt+1 has landed once only tiles kt+2 .. kt+NS-2 and the first half of tile kt+NS-1 are in flight;
-      // lgkmcnt(0): this wavefront holds all its fragments of tile kt
-      wait_vm_and_lds<(NS - 3) * LOADS_PER_TILE + LOADS_PER_TILE / 2>();
+      half_step(first, f0, f1, stage_at(sc), 1, 0, kt + NSTAGES - 1, lst);
+      // tile kt+1 has landed once only tiles kt+2 .. kt+NSTAGES-2 and A's requests of tile kt+NSTAGES-1 are in
+      // flight; lgkmcnt(0): this wavefront holds all its fragments of tile kt
+      wait_vm_and_lds<(NSTAGES - 3) * LOADS + REQS_A>();
       __builtin_amdgcn_s_barrier();
-      half_step(LATER, f1, f0, stage_at(after(sc)), 0, 1, kt + NS - 1, lst);
+      half_step(LATER, f1, f0, stage_at(after(sc)), 0, 1, kt + NSTAGES - 1, lst);
     };
     // Drain: the last (up to NS-1) tiles, nothing left to request.
     auto drain_step = [&](auto first, int kt, int sc) {
@@ -334,10 +351,10 @@ struct Pipe {
       __builtin_amdgcn_s_barrier();
       half_step(LATER, f1, f0, stage_at(after(sc)), 0, 1, -1, nullptr);   // past the last tile: stale data, never used
     };
-    int kt = 1, sc = 1 % NS;
-    if (NS - 1 < KT) {
+    int kt = 1, sc = 1 % NSTAGES;
+    if (NSTAGES - 1 < KT) {
       steady_step(FIRST, 0, 0);
-      for (; kt + NS - 1 < KT; ++kt, sc = after(sc)) steady_step(LATER, kt, sc);
+      for (; kt + NSTAGES - 1 < KT; ++kt, sc = after(sc)) steady_step(LATER, kt, sc);
     } else {
       drain_step(FIRST, 0, 0);
     }

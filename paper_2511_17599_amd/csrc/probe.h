@@ -12,12 +12,23 @@
 //                    fragment reads of every K step, issued side by side with no wait or barrier between them (the
 //                    fragments read are discarded): what the two streams reach when nothing makes one wait for the
 //                    other, i.e. how much of the complete loop's loss is synchronisation.
+//   PROBE_LOOP_KR_SOFTMAX : PROBE_LOOP_KR plus, after every tile, the plain-ALU work of the forward's tile
+//                    post-processing (per lane and column: a maximum over the column's accumulators, then the sum
+//                    of exp2 of their distances to it), with no overlap with the next tile's matrix work: one
+//                    wavefront per SIMD does both in turn.
+//   PROBE_HALF_KR / PROBE_HALF_KR_SOFTMAX : the same two on a 128 x 256 tile (A tile of half the height, 128
+//                    accumulators per lane, three stages, 72 KiB of LDS) with TWO workgroups per CU, so that one
+//                    workgroup's post-processing can overlap the other's matrix work.  Launch twice the workgroups
+//                    for the same total work.
 #pragma once
 #include "mainloop_fast.h"
 
 namespace flce {
 
-enum : int { PROBE_MFMA = 0, PROBE_LOOP_KR = 1, PROBE_LOOP_KC = 2, PROBE_DATA_KR = 3, PROBE_DATA_KC = 4, PROBE_FREE_RUN = 5 };
+enum : int {
+  PROBE_MFMA = 0, PROBE_LOOP_KR = 1, PROBE_LOOP_KC = 2, PROBE_DATA_KR = 3, PROBE_DATA_KC = 4, PROBE_FREE_RUN = 5,
+  PROBE_LOOP_KR_SOFTMAX = 6, PROBE_HALF_KR = 7, PROBE_HALF_KR_SOFTMAX = 8
+};
 
 struct ProbeArgs {
   const bf16_t* A;      // [a_rows][k_elems], K-contiguous (plays W)
@@ -27,6 +38,75 @@ struct ProbeArgs {
   int tiles_per_wg;     // tiles each workgroup walks along A (wrapping around a_rows)
   float* sink;          // [gridDim.x * 256] one float per thread, so that nothing is optimised away
 };
+
+// The arithmetic of one tile's softmax statistics on the accumulators as they lie in the registers (each lane holds,
+// per block column j, AM x 16 entries of one output column): the same instruction mix as the forward's tile
+// post-processing, minus its bookkeeping.
+template <int AM>
+__device__ __forceinline__ float softmax_work(f32x16 (&acc)[AM][fast::WN]) {
+  constexpr float LOG2E = 1.4426950408889634f;
+  float out = 0.f;
+#pragma unroll
+  for (int j = 0; j < fast::WN; ++j) {
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < AM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v;
+        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][r]));
+        m = fmaxf(m, v);
+      }
+    const float mc = m * LOG2E;
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < AM; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v;
+        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][r]));
+        sum += __builtin_amdgcn_exp2f(fmaf(v, LOG2E, -mc));
+      }
+    out += sum + m;
+  }
+  return out;
+}
+
+// 128 x 256 tiles, two workgroups per CU (at most 256 registers per lane, 72 KiB of LDS per workgroup).
+template <bool SOFTMAX>
+__global__ __launch_bounds__(fast::THREADS, 2) void probe_half_kernel(ProbeArgs p) {
+  extern __shared__ __align__(16) char lds[];
+  using HalfPipe = fast::Pipe<fast::KC, fast::KR, true, 2, 3>;
+  constexpr int AROWS = 128;
+  f32x16 acc[2][fast::WN];
+  const int n_at = p.a_rows / AROWS, n_bt = p.b_rows / TILE;
+  const int b0 = (blockIdx.x % n_bt) * TILE;
+  float keep = 0.f;
+  HalfPipe pipe;
+  const int64_t ld = (int64_t)p.k_elems * 2;
+  for (int t = 0; t < p.tiles_per_wg; ++t) {
+    const int a0 = ((blockIdx.x / n_bt + t) % n_at) * AROWS;
+    const fast::Operand As{reinterpret_cast<const char*>(p.A), ld, a0, p.a_rows, 0};
+    const fast::Operand Bs{reinterpret_cast<const char*>(p.BT) + (int64_t)b0 * 2, (int64_t)p.b_rows * 2, 0, p.k_elems,
+                           TILE * 2};
+    pipe.start(As, Bs, p.k_elems, lds);
+    pipe.run(lds, acc);
+    if constexpr (SOFTMAX) {
+      keep += softmax_work<2>(acc);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < fast::WN; ++j) {
+          float v;
+          asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][(i * 4 + j) & 15]));
+          keep += v;
+        }
+    }
+  }
+  p.sink[(int64_t)blockIdx.x * fast::THREADS + threadIdx.x] = keep;
+}
+constexpr int PROBE_HALF_LDS = fast::Pipe<fast::KC, fast::KR, true, 2, 3>::LDS_TOTAL;
 
 template <int MODE>
 __global__ __launch_bounds__(fast::THREADS) void probe_kernel(ProbeArgs p) {
@@ -118,8 +198,8 @@ __global__ __launch_bounds__(fast::THREADS) void probe_kernel(ProbeArgs p) {
     fast::wait_vm_and_lds<0>();
     __builtin_amdgcn_s_barrier();
   } else {
-    constexpr int LB = (MODE == PROBE_LOOP_KR || MODE == PROBE_DATA_KR) ? fast::KR : fast::KC;
-    constexpr bool MF = MODE == PROBE_LOOP_KR || MODE == PROBE_LOOP_KC;
+    constexpr int LB = (MODE == PROBE_LOOP_KR || MODE == PROBE_DATA_KR || MODE == PROBE_LOOP_KR_SOFTMAX) ? fast::KR : fast::KC;
+    constexpr bool MF = MODE == PROBE_LOOP_KR || MODE == PROBE_LOOP_KC || MODE == PROBE_LOOP_KR_SOFTMAX;
     fast::Pipe<fast::KC, LB, MF> pipe;
     const int64_t ld = (int64_t)p.k_elems * 2;
     for (int t = 0; t < p.tiles_per_wg; ++t) {
@@ -134,7 +214,9 @@ __global__ __launch_bounds__(fast::THREADS) void probe_kernel(ProbeArgs p) {
         pipe.start(As, Bs, p.k_elems, lds);
       }
       pipe.run(lds, acc);
-      if constexpr (MF) {
+      if constexpr (MODE == PROBE_LOOP_KR_SOFTMAX) {
+        keep += softmax_work<fast::WM>(acc);
+      } else if constexpr (MF) {
 #pragma unroll
         for (int i = 0; i < fast::WM; ++i)
 #pragma unroll
