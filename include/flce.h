@@ -338,6 +338,9 @@ flce_status flce_profile_collect(double* ms_by_class, int64_t* launches_by_class
  *   mode 7, 8 : modes 1 and 6 on tiles of 128 x 256 outputs (128 accumulators per lane, three stages) so that two
  *            workgroups share a CU and one's post-processing overlaps the other's matrix work; a tile is half
  *            the work, so these modes execute half the flops stated below per workgroup
+ *   mode 9 : mode 1 with every group of workgroups that shares an A tile walking a run of A tiles of its own, so
+ *            that each A tile is read once per launch, from HBM (the forward's access to W); in the other modes a
+ *            group reads what its neighbour read one tile earlier
  *   A  : device, bf16 [a_rows][k_elems];  B : device, bf16 [b_rows][k_elems];  BT : device, bf16 [k_elems][b_rows]
  *        (a_rows, b_rows multiples of 256, k_elems a multiple of 32); contents are the caller's choice of data.
  *   sink : device, workgroups * 256 floats, written once per thread.

@@ -83,6 +83,25 @@ struct Plan {
   int64_t off_Hc, off_rowmap, off_tgt, off_lsec, off_gamc, off_HT, off_WT, off_G, off_GT, off_dHacc, off_dWacc, off_partial, bwd_bytes;
 };
 
+// A contraction launch of more than one round of workgroups whose last round would be mostly empty: the output-row
+// tiles of that last round ("tail") are launched on their own with their K extent cut into `slices` slices (summed
+// in slice order by splitk_reduce_kernel, like any split-K launch), so that the tail takes 1 / slices of a round.
+// rows = 0: no tail (one round or less; more than four rounds, where the last one matters little and the partial
+// sums would cost workspace for it; a last round that is more than half full; a launch that is split anyway).
+struct TailSplit { int rows, slices; };
+TailSplit tail_split(int64_t out_row_tiles, int64_t n_mt, int n_split, int64_t k_tiles) {
+  if (n_split != 1) return {0, 1};
+  const int64_t tiles = out_row_tiles * n_mt;
+  if (tiles <= NUM_CU || tiles > 4 * NUM_CU) return {0, 1};
+  const int64_t body_rows = tiles / NUM_CU * NUM_CU / n_mt;
+  const int64_t rows = out_row_tiles - body_rows;
+  if (rows <= 0 || body_rows <= 0) return {0, 1};
+  // whole slices of at least two 256-element K tiles each, at most 8
+  const int64_t slices = std::min<int64_t>(std::min<int64_t>(NUM_CU / (rows * n_mt), 8), k_tiles / 2);
+  if (slices < 2) return {0, 1};
+  return {(int)rows, (int)slices};
+}
+
 // The tuned bf16 loop needs K extents that are multiples of 32 elements and every tile's address
 // window within reach of a buffer descriptor: offsets and the record count are unsigned 32-bit, and
 // the zero-filled overshoot of a last K stage (up to 32 rows) must not wrap 2^32.
@@ -194,6 +213,16 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p, bool all
     int64_t bytes = 0;
     if (p.split_dh > 1) bytes = std::max(bytes, (int64_t)p.split_dh * nc_pad * d * 4);
     if (p.split_dw > 1) bytes = std::max(bytes, (int64_t)p.split_dw * vc_pad * d * 4);
+    if (p.fast) {
+      // tails of the launches that occur: full chunks and the last (shorter) chunk of either direction
+      const int64_t v_last = p.n_vt - (int64_t)(p.n_vch - 1) * p.vc_tiles, n_last = p.n_rb - (int64_t)(p.n_nch - 1) * p.nc_tiles;
+      for (const int64_t vt : {(int64_t)p.vc_tiles, v_last})
+        for (const int64_t nt : {(int64_t)p.nc_tiles, n_last}) {
+          const TailSplit tw = tail_split(vt, n_mt, p.split_dw, nt), th = tail_split(nt, n_mt, p.split_dh, vt);
+          if (tw.rows) bytes = std::max(bytes, (int64_t)tw.slices * tw.rows * TILE * d * 4);
+          if (th.rows) bytes = std::max(bytes, (int64_t)th.slices * th.rows * TILE * d * 4);
+        }
+    }
     o = align_up(o + bytes, ALIGN);
   }
   p.bwd_bytes = o;
@@ -441,6 +470,38 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
                              slice_len(n_vt * TILE, p.split_dh), partial - (int64_t)nt0 * TILE * d, nc_pad * d};
   };
 
+  // One contraction (dW or dH) of a chunk: the launch, its split-K sum if it has one, and with the tuned loop a
+  // separately launched, K-split tail when the last round of workgroups would be mostly empty (tail_split).
+  auto contract = [&](const ContractArgs<T>& a, bool is_dw) {
+    auto launch = [&](const ContractArgs<T>& x) {
+      if constexpr (L::TRANSPOSING) {
+        const int grid = std::min(x.n_nt * x.n_mt * x.n_split, NUM_CU);
+        if (is_dw) contract_kernel<T, L, OPS_DW_TR><<<grid, L::THREADS, L::LDS, st>>>(x);
+        else contract_kernel<T, L, OPS_DH_TR><<<grid, L::THREADS, L::LDS, st>>>(x);
+      } else {
+        contract_kernel<T, L, OPS_KC><<<x.n_nt * x.n_mt * x.n_split, L::THREADS, L::LDS, st>>>(x);
+      }
+      if (x.n_split > 1) splitk_reduce_kernel<T><<<x.n_nt * TILE, 256, 0, st>>>(x);
+    };
+    TailSplit ts{0, 1};
+    if constexpr (L::TRANSPOSING) ts = tail_split(a.n_nt, a.n_mt, a.n_split, a.k_elems / TILE);
+    if (!ts.rows) { launch(a); return; }
+    ContractArgs<T> body = a, tail = a;
+    body.n_nt = a.n_nt - ts.rows;
+    const int64_t first = (int64_t)body.n_nt * TILE;     // the tail's first output row, relative to the launch's
+    tail.n_nt = ts.rows;
+    tail.out_row0 = a.out_row0 + (int)first;
+    // G is the B operand of both: its columns are dW's output rows, its rows are dH's
+    if (is_dw) { tail.B = a.B + first; }
+    else { tail.B = a.B + first * a.ldb; tail.b_rows = a.b_rows - (int)first; }
+    tail.n_split = ts.slices;
+    tail.k_split = slice_len(a.k_elems, ts.slices);
+    tail.partial = a.partial - first * a.d;                // indexed like accbuf: by output row from the launch's first
+    tail.partial_stride = (int64_t)ts.rows * TILE * a.d;
+    launch(body);
+    launch(tail);
+  };
+
   for (int vc = 0; vc < p.n_vch; ++vc) {
     int vt0, n_vt;
     chunk_vt(vc, vt0, n_vt);
@@ -467,22 +528,12 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
         }
       }
       {
-        const ContractArgs<T> a = dw_args(vc, nc, G);
         ProfScope ps(FLCE_PROF_CONTRACT_DW, st);
-        if constexpr (L::TRANSPOSING)
-          contract_kernel<T, L, OPS_DW_TR><<<std::min(a.n_nt * a.n_mt * a.n_split, NUM_CU), L::THREADS, L::LDS, st>>>(a);
-        else
-          contract_kernel<T, L, OPS_KC><<<a.n_nt * a.n_mt * a.n_split, L::THREADS, L::LDS, st>>>(a);
-        if (a.n_split > 1) splitk_reduce_kernel<T><<<a.n_nt * TILE, 256, 0, st>>>(a);
+        contract(dw_args(vc, nc, G), true);
       }
       {
-        const ContractArgs<T> a = dh_args(vc, nc, G);
         ProfScope ps(FLCE_PROF_CONTRACT_DH, st);
-        if constexpr (L::TRANSPOSING)
-          contract_kernel<T, L, OPS_DH_TR><<<std::min(a.n_nt * a.n_mt * a.n_split, NUM_CU), L::THREADS, L::LDS, st>>>(a);
-        else
-          contract_kernel<T, L, OPS_KC><<<a.n_nt * a.n_mt * a.n_split, L::THREADS, L::LDS, st>>>(a);
-        if (a.n_split > 1) splitk_reduce_kernel<T><<<a.n_nt * TILE, 256, 0, st>>>(a);
+        contract(dh_args(vc, nc, G), false);
       }
     }
   }
@@ -553,11 +604,18 @@ const char* flce_status_string(flce_status s) {
 int flce_plan_describe(int64_t N, int64_t d, int64_t V, flce_dtype dt, char* buf, size_t buf_bytes) {
   flce::Plan p;
   if (!buf || buf_bytes == 0 || !flce::make_plan(N, d, V, dt, p)) return -1;
+  // K-split tails of the contraction launches of a full chunk (output-row tiles x slices; 0x1 = none)
+  const int64_t n_mt = (d + flce::TILE - 1) / flce::TILE;
+  flce::TailSplit th{0, 1}, tw{0, 1};
+  if (p.fast) {
+    th = flce::tail_split(p.nc_tiles, n_mt, p.split_dh, p.vc_tiles);
+    tw = flce::tail_split(p.vc_tiles, n_mt, p.split_dw, p.nc_tiles);
+  }
   return std::snprintf(buf, buf_bytes,
                        "flce %s loop=%s h_copy=%d windows=%d vocab_chunks=%dx%d row_chunks=%dx%d splitk_dH=%d splitk_dW=%d "
-                       "staging_bytes=%lld fwd_ws=%lld bwd_ws=%lld",
+                       "tail_dH=%dx%d tail_dW=%dx%d staging_bytes=%lld fwd_ws=%lld bwd_ws=%lld",
                        flce_version(), p.fast ? "tuned" : "generic", p.hkr ? 1 : 0, p.n_win, p.n_vch, p.vc_tiles, p.n_nch,
-                       p.nc_tiles, p.split_dh, p.split_dw,
+                       p.nc_tiles, p.split_dh, p.split_dw, th.rows, th.slices, tw.rows, tw.slices,
                        (long long)((int64_t)p.nc_tiles * flce::TILE * p.ld_v * p.esize), (long long)p.fwd_bytes,
                        (long long)p.bwd_bytes);
 }
@@ -803,7 +861,7 @@ flce_status flce_last_device_status(const void* workspace, void* hip_stream, int
 flce_status flce_probe(int mode, const void* A, const void* B, const void* BT, int64_t a_rows, int64_t b_rows,
                        int64_t k_elems, int workgroups, int tiles_per_workgroup, float* sink, void* hip_stream) {
   if (!A || !B || !BT || !sink) return FLCE_ERR_BAD_ARG;
-  if (mode < flce::PROBE_MFMA || mode > flce::PROBE_HALF_KR_SOFTMAX) return FLCE_ERR_BAD_ARG;
+  if (mode < flce::PROBE_MFMA || mode > flce::PROBE_LOOP_KR_COLD) return FLCE_ERR_BAD_ARG;
   if (a_rows <= 0 || b_rows <= 0 || (a_rows % flce::TILE) || (b_rows % flce::TILE) || k_elems < 32 || (k_elems % 32) ||
       workgroups <= 0 || tiles_per_workgroup <= 0)
     return FLCE_ERR_BAD_SHAPE;
@@ -828,6 +886,7 @@ flce_status flce_probe(int mode, const void* A, const void* B, const void* BT, i
     case flce::PROBE_LOOP_KR_SOFTMAX: return launch(flce::probe_kernel<flce::PROBE_LOOP_KR_SOFTMAX>);
     case flce::PROBE_HALF_KR: return launch(flce::probe_half_kernel<false>, flce::PROBE_HALF_LDS);
     case flce::PROBE_HALF_KR_SOFTMAX: return launch(flce::probe_half_kernel<true>, flce::PROBE_HALF_LDS);
+    case flce::PROBE_LOOP_KR_COLD: return launch(flce::probe_kernel<flce::PROBE_LOOP_KR_COLD>);
   }
   return FLCE_ERR_BAD_ARG;
 }

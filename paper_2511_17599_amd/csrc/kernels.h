@@ -342,8 +342,11 @@ __device__ __forceinline__ void merge_parts_of_row(const float* __restrict__ pm,
                                                    const float* __restrict__ pz, int n_parts, int64_t stride, int n,
                                                    float& M, float& A, float& z) {
   M = NEG_INF;
-  for (int w = 0; w < n_parts; ++w)
-    if (pa[(int64_t)w * stride + n] > 0.f) M = fmaxf(M, pm[(int64_t)w * stride + n]);
+  // both loads of a part are unconditional, so that the loads of all parts can be in flight together
+  for (int w = 0; w < n_parts; ++w) {
+    const float mw = pm[(int64_t)w * stride + n], aw = pa[(int64_t)w * stride + n];
+    M = aw > 0.f ? fmaxf(M, mw) : M;
+  }
   A = 0.f; z = 0.f;
   for (int w = 0; w < n_parts; ++w) {
     const float mw = pm[(int64_t)w * stride + n], aw = pa[(int64_t)w * stride + n];

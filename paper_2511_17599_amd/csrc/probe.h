@@ -20,6 +20,10 @@
 //                    accumulators per lane, three stages, 72 KiB of LDS) with TWO workgroups per CU, so that one
 //                    workgroup's post-processing can overlap the other's matrix work.  Launch twice the workgroups
 //                    for the same total work.
+//   PROBE_LOOP_KR_COLD : PROBE_LOOP_KR with every group of workgroups walking its own contiguous run of A tiles, so
+//                    that no A tile is read twice in a launch (the other modes walk overlapping runs: what one group
+//                    reads, its neighbour read one tile earlier and the caches still hold it).  This is how the
+//                    forward reads W: every tile comes from HBM.
 #pragma once
 #include "mainloop_fast.h"
 
@@ -27,7 +31,7 @@ namespace flce {
 
 enum : int {
   PROBE_MFMA = 0, PROBE_LOOP_KR = 1, PROBE_LOOP_KC = 2, PROBE_DATA_KR = 3, PROBE_DATA_KC = 4, PROBE_FREE_RUN = 5,
-  PROBE_LOOP_KR_SOFTMAX = 6, PROBE_HALF_KR = 7, PROBE_HALF_KR_SOFTMAX = 8
+  PROBE_LOOP_KR_SOFTMAX = 6, PROBE_HALF_KR = 7, PROBE_HALF_KR_SOFTMAX = 8, PROBE_LOOP_KR_COLD = 9
 };
 
 struct ProbeArgs {
@@ -198,12 +202,13 @@ __global__ __launch_bounds__(fast::THREADS) void probe_kernel(ProbeArgs p) {
     fast::wait_vm_and_lds<0>();
     __builtin_amdgcn_s_barrier();
   } else {
-    constexpr int LB = (MODE == PROBE_LOOP_KR || MODE == PROBE_DATA_KR || MODE == PROBE_LOOP_KR_SOFTMAX) ? fast::KR : fast::KC;
-    constexpr bool MF = MODE == PROBE_LOOP_KR || MODE == PROBE_LOOP_KC || MODE == PROBE_LOOP_KR_SOFTMAX;
+    constexpr int LB = (MODE == PROBE_LOOP_KR || MODE == PROBE_DATA_KR || MODE == PROBE_LOOP_KR_SOFTMAX || MODE == PROBE_LOOP_KR_COLD) ? fast::KR : fast::KC;
+    constexpr bool MF = MODE == PROBE_LOOP_KR || MODE == PROBE_LOOP_KC || MODE == PROBE_LOOP_KR_SOFTMAX || MODE == PROBE_LOOP_KR_COLD;
     fast::Pipe<fast::KC, LB, MF> pipe;
     const int64_t ld = (int64_t)p.k_elems * 2;
     for (int t = 0; t < p.tiles_per_wg; ++t) {
-      const int a0 = ((blockIdx.x / n_bt + t) % n_at) * TILE;
+      const int a0 = (MODE == PROBE_LOOP_KR_COLD ? (blockIdx.x / n_bt * p.tiles_per_wg + t) % n_at
+                                                 : (blockIdx.x / n_bt + t) % n_at) * TILE;
       const fast::Operand As{reinterpret_cast<const char*>(p.A), ld, a0, p.a_rows, 0};
       if constexpr (LB == fast::KR) {
         const fast::Operand Bs{reinterpret_cast<const char*>(p.BT) + (int64_t)b0 * 2, (int64_t)p.b_rows * 2, 0,

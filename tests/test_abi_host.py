@@ -94,7 +94,7 @@ def test_probe_and_plan_reject_bad_shapes_on_the_host():
     p = 4096
     assert B.flce_probe(0, p, p, p, 256, 256, 31, 4, 1, p) == B.FLCE_ERR_BAD_SHAPE       # K not a multiple of 32
     assert B.flce_probe(0, p, p, p, 250, 256, 64, 4, 1, p) == B.FLCE_ERR_BAD_SHAPE       # rows not whole tiles
-    assert B.flce_probe(9, p, p, p, 256, 256, 64, 4, 1, p) == B.FLCE_ERR_BAD_ARG         # unknown mode
+    assert B.flce_probe(len(B.PROBE_MODES), p, p, p, 256, 256, 64, 4, 1, p) == B.FLCE_ERR_BAD_ARG   # unknown mode
     assert B.flce_probe(0, None, p, p, 256, 256, 64, 4, 1, p) == B.FLCE_ERR_BAD_ARG
     with pytest.raises(ValueError):
         B.flce_plan_describe(64, 60, 64, B.FLCE_DTYPE_BF16)

@@ -113,6 +113,25 @@ def test_split_k_contractions(monkeypatch, dtype, generic, sdh, sdw, vc, nc):
     check_against_oracle(wl, I.make_inputs(wl))
 
 
+@pytest.mark.parametrize("name,N,d,V,ignore_frac", [
+    # dW: 90 x 3 = 270 output tiles = one round of 256 workgroups + 5 output-row tiles (15 tiles) cut into 2 K slices
+    ("tail_dW", 1024, 768, 23040, 0.1),
+    # dH: 20 x 14 = 280 output tiles = one round + 2 row tiles (28 tiles) cut into 4 K slices; with a twentieth of
+    # the rows ignored the compacted rows end inside the tail
+    ("tail_dH", 5120, 3584, 2048, 0.05),
+    # the same with so many rows ignored that the tail launch has no rows left at all
+    ("tail_dH_empty", 5120, 3584, 2048, 0.15),
+])
+def test_k_split_tail_of_a_contraction_launch(name, N, d, V, ignore_frac):
+    """Launches of a little more than one round of workgroups: the output-row tiles beyond the whole rounds go
+    out as a second launch with K cut into slices (default plan; the plan line says which tails it has)."""
+    plan = B.flce_plan_describe(N, d, V, B.FLCE_DTYPE_BF16)
+    print(plan, flush=True)
+    assert ("tail_dW=5x2" in plan) if name == "tail_dW" else ("tail_dH=2x4" in plan)
+    wl = custom(name, N, d, V, "bf16", 25, ignore_frac=ignore_frac)
+    check_against_oracle(wl, I.make_inputs(wl))
+
+
 @pytest.mark.parametrize("d", [32, 96, 416])
 def test_tuned_loop_short_and_odd_k(d):
     """K extents of 1, 3 and 13 stages of the tuned bf16 loop (prologue / drain paths), hidden size not a
@@ -189,10 +208,14 @@ def test_out_of_range_target_is_flagged_and_dropped():
     # summed by the second kernel: the places where an order that depended on scheduling would show
     {"FLCE_VC_TILES": "2", "FLCE_NC_TILES": "2", "FLCE_SPLITK_DH": "3", "FLCE_SPLITK_DW": "2", "FLCE_WINDOWS": "5"},
     {"FLCE_VC_TILES": "3", "FLCE_NC_TILES": "1", "FLCE_SPLITK_DH": "2", "FLCE_SPLITK_DW": "1", "FLCE_GENERIC": "1"},
-], ids=["default_plan", "chunks_and_k_slices", "generic_loop_chunks"])
+    # a dW launch with a K-split tail (90 x 3 output tiles)
+    {"shape": (1024, 768, 23040)},
+], ids=["default_plan", "chunks_and_k_slices", "generic_loop_chunks", "k_split_tail"])
 def test_results_are_bit_identical_between_runs(monkeypatch, env):
+    env = dict(env)
+    N, d, V = env.pop("shape", (1024, 256, 5000))
     set_plan(monkeypatch, **env)
-    wl = custom("determinism", 1024, 256, 5000, "bf16", 61, targets="zipf", ignore_frac=0.05)
+    wl = custom("determinism", N, d, V, "bf16", 61, targets="zipf", ignore_frac=0.05)
     x = I.make_inputs(wl)
     a = run_workload(wl, x)
     b = run_workload(wl, x)
