@@ -341,17 +341,36 @@ __device__ __forceinline__ float block_sum_256(float v, float* sh) {
 __device__ __forceinline__ void merge_parts_of_row(const float* __restrict__ pm, const float* __restrict__ pa,
                                                    const float* __restrict__ pz, int n_parts, int64_t stride, int n,
                                                    float& M, float& A, float& z) {
+  // The parts are taken eight at a time with all their loads issued before the first use (a part past the end
+  // re-reads the last one and is not used): the parts of one row lie in different memory rows, and a load per loop
+  // trip would make the merge wait for memory once per part.  The arithmetic and its order are those of the plain loop.
+  constexpr int U = 8;
   M = NEG_INF;
-  // both loads of a part are unconditional, so that the loads of all parts can be in flight together
-  for (int w = 0; w < n_parts; ++w) {
-    const float mw = pm[(int64_t)w * stride + n], aw = pa[(int64_t)w * stride + n];
-    M = aw > 0.f ? fmaxf(M, mw) : M;
+  for (int w0 = 0; w0 < n_parts; w0 += U) {
+    float mw[U], aw[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t o = (int64_t)min(w0 + u, n_parts - 1) * stride + n;
+      mw[u] = pm[o]; aw[u] = pa[o];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (w0 + u < n_parts && aw[u] > 0.f) M = fmaxf(M, mw[u]);
   }
   A = 0.f; z = 0.f;
-  for (int w = 0; w < n_parts; ++w) {
-    const float mw = pm[(int64_t)w * stride + n], aw = pa[(int64_t)w * stride + n];
-    if (aw > 0.f) A += aw * fast_exp2((mw - M) * LOG2E);
-    z += pz[(int64_t)w * stride + n];
+  for (int w0 = 0; w0 < n_parts; w0 += U) {
+    float mw[U], aw[U], zw[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t o = (int64_t)min(w0 + u, n_parts - 1) * stride + n;
+      mw[u] = pm[o]; aw[u] = pa[o]; zw[u] = pz[o];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (w0 + u < n_parts) {
+        if (aw[u] > 0.f) A += aw[u] * fast_exp2((mw[u] - M) * LOG2E);
+        z += zw[u];
+      }
   }
 }
 
