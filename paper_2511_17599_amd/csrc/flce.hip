@@ -393,21 +393,17 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
   const int64_t vc_pad = (int64_t)p.vc_tiles * TILE, nc_pad = (int64_t)p.nc_tiles * TILE;
   const int n_mt = (int)ceil_div(d, TILE);
   const int npad = (int)p.npad;
-  const int64_t row_bytes = (int64_t)d * sizeof(T);
 
   {
     ProfScope ps(FLCE_PROF_BWD_PREP, st);
     compact_targets_kernel<<<1, 1024, 0, st>>>(y, N, V, slice.V_total, slice.v_begin, ignore_index, npad, rowmap,
                                                tgt_c, hdr);
-    gather_rows_kernel<<<npad, 256, 0, st>>>(static_cast<const char*>(H), row_bytes, rowmap, lse,
-                                             reinterpret_cast<char*>(Hc), lse_c, rows.grad_rows, gam_c);
-    zero_uncounted_rows_kernel<<<N, 256, 0, st>>>(y, slice.V_total, ignore_index, static_cast<char*>(dH), row_bytes);
-    if (!L::TRANSPOSING || p.hkr) {
-      // Hc^T [d][npad]: the dW contraction's K-contiguous operand (generic loop), or the recompute's
-      // operand read across memory rows (tuned loop)
-      transpose_pad_kernel<U><<<dim3((unsigned)ceil_div(p.npad, 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
-          reinterpret_cast<const U*>(Hc), d, npad, 0, d, reinterpret_cast<U*>(HT), p.npad, npad);
-    }
+    // Hc (and Hc^T [d][npad]: the dW contraction's K-contiguous operand with the generic loop, the recompute's
+    // operand read across memory rows with the tuned loop), lse and Gamma per compact row, zero rows of dH
+    const bool need_t = !L::TRANSPOSING || p.hkr;
+    prep_rows_kernel<U><<<dim3((unsigned)(p.npad / 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
+        static_cast<const U*>(H), d, rowmap, reinterpret_cast<U*>(Hc), need_t ? reinterpret_cast<U*>(HT) : nullptr,
+        p.npad, lse, lse_c, rows.grad_rows, gam_c, y, N, slice.V_total, ignore_index, static_cast<U*>(dH));
   }
 
   bool hkr = false;

@@ -5,11 +5,11 @@
 //             vocabulary window: Section 3.2.1)
 //             merge_rows_kernel + finalize_loss_kernel (the merging epilogue of
 //             Section 3.2.1, lse = m + ln a, per-row loss, fixed-order sums)
-//   backward: compact_targets_kernel + gather_rows_kernel (n_valid, range flag, and the
-//             rows that count packed together: ignored rows have a zero row of G)
-//             transpose_pad_kernel (the transposed copy of H that the tuned main loop
-//             reads across memory rows; with the generic loop also the K-contiguous
-//             copies of W and H that the two gradient contractions need)
+//   backward: compact_targets_kernel + prep_rows_kernel (n_valid, range flag, and the
+//             rows that count packed together: ignored rows have a zero row of G; the
+//             packed rows also transposed for a main loop that reads that copy)
+//             transpose_pad_kernel (the forward's transposed copy of H; with the generic
+//             loop also the K-contiguous copy of W that the dH contraction needs)
 //             recompute_kernel (Alg. 2: z recomputed, g = p - onehot, staged once in a
 //             fixed-size buffer; the generic loop also stages the transpose)
 //             contract_kernel (Eq. 4 and Eq. 5 as output-stationary MFMA
@@ -549,39 +549,55 @@ __global__ __launch_bounds__(1024) void compact_targets_kernel(const int64_t* __
   }
 }
 
-// Hc[c][:] = H[rowmap[c]][:], lse_c[c] = lse[rowmap[c]] (and the row's upstream gradient, if given); zero rows
-// where rowmap[c] < 0.
-// One block per compact row; rows are copied as 16-byte vectors (row_bytes % 16 == 0).
-__global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict__ H, int64_t row_bytes,
-                                                          const int* __restrict__ rowmap,
-                                                          const float* __restrict__ lse, char* __restrict__ Hc,
-                                                          float* __restrict__ lse_c,
-                                                          const float* __restrict__ grad_rows,
-                                                          float* __restrict__ gam_c) {
-  const int c = blockIdx.x;
-  const int n = rowmap[c];
-  const u32x4 z = {0u, 0u, 0u, 0u};
-  const u32x4* src = reinterpret_cast<const u32x4*>(H + (int64_t)(n < 0 ? 0 : n) * row_bytes);
-  u32x4* dst = reinterpret_cast<u32x4*>(Hc + (int64_t)c * row_bytes);
-  const int nvec = (int)(row_bytes / 16);
-  for (int i = threadIdx.x; i < nvec; i += 256) dst[i] = (n >= 0) ? src[i] : z;
-  if (threadIdx.x == 0) {
-    lse_c[c] = (n >= 0) ? lse[n] : 0.f;
-    if (grad_rows) gam_c[c] = (n >= 0) ? grad_rows[n] : 0.f;
+// The backward's row preparation, one launch, 64 compact rows x 64 hidden positions per block:
+//   Hc[c][:]  = H[rowmap[c]][:], zero for the padding rows behind the last counted row;
+//   HcT[:][c] = the same transposed, when a main loop reads that copy (HcT != nullptr; ld_t elements per row);
+//   lse_c[c], gam_c[c] = the row's log-sum-exp and (per-row variant) upstream gradient, 0 for padding rows;
+//   dH[n][:]  = exactly +0 for every token n that does not count (the contractions write the counted rows only).
+// U is an unsigned integer type of the element's width (pure data movement).
+template <typename U>
+__global__ __launch_bounds__(256) void prep_rows_kernel(const U* __restrict__ H, int d, const int* __restrict__ rowmap,
+                                                        U* __restrict__ Hc, U* __restrict__ HcT, int64_t ld_t,
+                                                        const float* __restrict__ lse, float* __restrict__ lse_c,
+                                                        const float* __restrict__ grad_rows, float* __restrict__ gam_c,
+                                                        const int64_t* __restrict__ y, int N, int64_t V_total,
+                                                        int64_t ignore_index, U* __restrict__ dH) {
+  __shared__ U tile[64][65];
+  __shared__ int src_row[64];
+  __shared__ int dead[64];
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int rb = blockIdx.x * 64, cb = blockIdx.y * 64;
+  if (threadIdx.x < 64) {
+    const int r = rb + (int)threadIdx.x;               // a compact row, and also token r of the original order
+    const int n = rowmap[r];
+    src_row[threadIdx.x] = n;
+    bool oor;
+    dead[threadIdx.x] = (r < N && !target_counts(y[r], ignore_index, V_total, oor)) ? 1 : 0;
+    if (blockIdx.y == 0) {
+      lse_c[r] = (n >= 0) ? lse[n] : 0.f;
+      if (grad_rows) gam_c[r] = (n >= 0) ? grad_rows[n] : 0.f;
+    }
   }
-}
-
-// dH rows of tokens that do not count are exactly +0.  One block per row.
-__global__ __launch_bounds__(256) void zero_uncounted_rows_kernel(const int64_t* __restrict__ y, int64_t V_total,
-                                                                  int64_t ignore_index, char* __restrict__ dH,
-                                                                  int64_t row_bytes) {
-  const int n = blockIdx.x;
-  bool oor;
-  if (target_counts(y[n], ignore_index, V_total, oor)) return;
-  const u32x4 z = {0u, 0u, 0u, 0u};
-  u32x4* dst = reinterpret_cast<u32x4*>(dH + (int64_t)n * row_bytes);
-  const int nvec = (int)(row_bytes / 16);
-  for (int i = threadIdx.x; i < nvec; i += 256) dst[i] = z;
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const int rr = ty + 4 * k, r = rb + rr, c = cb + tx;
+    const int n = src_row[rr];
+    U v = 0;
+    if (c < d) {
+      if (n >= 0) v = H[(int64_t)n * d + c];
+      Hc[(int64_t)r * d + c] = v;
+      if (dead[rr]) dH[(int64_t)r * d + c] = 0;
+    }
+    tile[rr][tx] = v;
+  }
+  if (HcT == nullptr) return;
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 16; ++k) {
+    const int c = cb + ty + 4 * k, r = rb + tx;
+    if (c < d) HcT[(int64_t)c * ld_t + r] = tile[tx][ty + 4 * k];
+  }
 }
 
 // dst[c][r] = src[r0 + r][c]  for c < cols, r < rows_pad; zero where r0 + r >= rows_total.
