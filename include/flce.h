@@ -341,6 +341,7 @@ flce_status flce_profile_collect(double* ms_by_class, int64_t* launches_by_class
  *   mode 9 : mode 1 with every group of workgroups that shares an A tile walking a run of A tiles of its own, so
  *            that each A tile is read once per launch, from HBM (the forward's access to W); in the other modes a
  *            group reads what its neighbour read one tile earlier
+ *   mode 10 : mode 0 with the 16x16x32 bf16 MFMA (64 blocks of 4 accumulators per wavefront instead of 16 of 16)
  *   A  : device, bf16 [a_rows][k_elems];  B : device, bf16 [b_rows][k_elems];  BT : device, bf16 [k_elems][b_rows]
  *        (a_rows, b_rows multiples of 256, k_elems a multiple of 32); contents are the caller's choice of data.
  *   sink : device, workgroups * 256 floats, written once per thread.

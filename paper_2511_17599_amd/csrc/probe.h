@@ -24,6 +24,9 @@
 //                    that no A tile is read twice in a launch (the other modes walk overlapping runs: what one group
 //                    reads, its neighbour read one tile earlier and the caches still hold it).  This is how the
 //                    forward reads W: every tile comes from HBM.
+//   PROBE_MFMA_16X16 : PROBE_MFMA with the 16x16x32 bf16 MFMA instead (8 x 8 blocks of 4 accumulators per wavefront:
+//                    the same 128 x 128 sub-tile, the same flops per fragment, a quarter of the accumulator
+//                    registers read and written per instruction).
 #pragma once
 #include "mainloop_fast.h"
 
@@ -31,7 +34,7 @@ namespace flce {
 
 enum : int {
   PROBE_MFMA = 0, PROBE_LOOP_KR = 1, PROBE_LOOP_KC = 2, PROBE_DATA_KR = 3, PROBE_DATA_KC = 4, PROBE_FREE_RUN = 5,
-  PROBE_LOOP_KR_SOFTMAX = 6, PROBE_HALF_KR = 7, PROBE_HALF_KR_SOFTMAX = 8, PROBE_LOOP_KR_COLD = 9
+  PROBE_LOOP_KR_SOFTMAX = 6, PROBE_HALF_KR = 7, PROBE_HALF_KR_SOFTMAX = 8, PROBE_LOOP_KR_COLD = 9, PROBE_MFMA_16X16 = 10
 };
 
 struct ProbeArgs {
@@ -74,6 +77,44 @@ __device__ __forceinline__ float softmax_work(f32x16 (&acc)[AM][fast::WN]) {
     out += sum + m;
   }
   return out;
+}
+
+typedef __attribute__((ext_vector_type(4))) float f32x4_probe;
+
+template <int UNUSED = 0>
+__global__ __launch_bounds__(fast::THREADS) void probe_mfma16_kernel(ProbeArgs p) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int b0 = (blockIdx.x % (p.b_rows / TILE)) * TILE;
+  bf16x8 fa[8], fb[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    fa[i] = *reinterpret_cast<const bf16x8*>(p.A + (int64_t)((wave * 8 + i) * 64 + lane) % p.a_rows * p.k_elems);
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    fb[j] = *reinterpret_cast<const bf16x8*>(p.B + (int64_t)(b0 + (wave * 8 + j) * 64 % TILE + lane) % p.b_rows * p.k_elems);
+  f32x4_probe acc[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = f32x4_probe{0.f, 0.f, 0.f, 0.f};
+  const int steps = p.tiles_per_wg * (p.k_elems / 32);       // MFMA K steps (32 deep) of all tiles
+  for (int s = 0; s < steps; ++s) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+  }
+  float keep = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float v;
+      asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][0]));
+      keep += v;
+    }
+  p.sink[(int64_t)blockIdx.x * fast::THREADS + threadIdx.x] = keep;
 }
 
 // 128 x 256 tiles, two workgroups per CU (at most 256 registers per lane, 72 KiB of LDS per workgroup).
