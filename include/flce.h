@@ -112,7 +112,8 @@ const char* flce_status_string(flce_status s);
  *               Nc * Vc stays within 2^25 elements there): at most 2 GiB + 4 MiB in bf16 whatever N and V,
  *               512 MiB at N = 8192; below the cap this IS Npad x Vpad, the whole G in the storage type;
  *             + fp32 running sums N * d (more than one vocabulary chunk) and Vc * d (more than one row chunk)
- *             + fp32 K-slice tiles when a contraction launch is split (small N or small d);
+ *             + fp32 K-slice tiles when a contraction launch is split (small N or small d), or when the output-row
+ *               tiles of its last, mostly empty round are launched on their own with K in slices (at most 64 MiB);
  *             the generic loop (fp32, or bf16 with d % 32 != 0) adds transposed copies of a W chunk and of G.
  *   Beyond the cap the size grows like c1 * (N + V) * d + c2 * N + c3: no N * V term.  flce_plan_describe
  *   prints the staging bytes of a shape.
@@ -121,7 +122,8 @@ size_t flce_workspace_bytes(int64_t N, int64_t d, int64_t V, flce_dtype dt, int 
 
 /*
  * Writes a one-line description of the launch plan at this shape (library version, main loop, windows,
- * chunk counts x largest chunk in 256-row tiles, K slices, staging and workspace bytes) into `buf`; returns
+ * chunk counts x largest chunk in 256-row tiles, K slices, K-split tails of a full chunk's dH / dW launch as
+ * output-row tiles x slices, staging and workspace bytes) into `buf`; returns
  * the length it needs (as snprintf) or -1 for an invalid shape.  Reports and profile summaries carry it, so
  * that a measurement can be matched to the plan it was taken on.  Host call.
  */
