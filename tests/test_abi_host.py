@@ -101,6 +101,31 @@ def test_probe_and_plan_reject_bad_shapes_on_the_host():
     assert "windows=" in B.flce_plan_describe(64, 64, 64, B.FLCE_DTYPE_BF16)
 
 
+def _plan(N, d, V):
+    return dict(kv.split("=") for kv in B.flce_plan_describe(N, d, V, B.FLCE_DTYPE_BF16).split()[2:])
+
+
+def test_k_split_tails_are_planned_where_a_last_round_is_mostly_empty():
+    """A contraction launch of one to four rounds of 256 output tiles with a last round less than half full gets a
+    K-split tail (output-row tiles x slices); its slices fill at most one round and cost at most 64 MiB."""
+    # GPT-2 shape: dW has 197 x 3 = 591 tiles: 170 row tiles whole (510 tiles), 27 in 3 slices (243 workgroups)
+    assert _plan(4096, 768, 50257)["tail_dW"] == "27x3"
+    # Llama shape: dW 128 x 16 = 2048 tiles = 8 rounds (none: too many rounds), dH 32 x 16 = 2 rounds exactly
+    p = _plan(8192, 4096, 128256)
+    assert p["tail_dW"] == "0x1" and p["tail_dH"] == "0x1"
+    # a launch that is K-split as a whole has no tail on top
+    p = _plan(8192, 3072, 256000)
+    assert p["splitk_dH"] == "2" and p["tail_dH"] == "0x1"
+    for N, d, V in [(1024, 768, 23040), (5120, 3584, 2048), (4096, 768, 50257), (2048, 1024, 40000), (3072, 512, 70000)]:
+        p = _plan(N, d, V)
+        n_mt = -(-d // 256)
+        for key in ("tail_dH", "tail_dW"):
+            rows, slices = map(int, p[key].split("x"))
+            if rows:
+                assert slices >= 2 and rows * n_mt * slices <= 256
+                assert slices * rows * 256 * d * 4 <= 64 << 20
+
+
 @pytest.mark.parametrize("N,d,V", [(0, 64, 64), (64, 0, 64), (64, 64, 0), (64, 60, 64), (-1, 64, 64)])
 def test_bad_shapes_are_rejected(N, d, V):
     assert B.flce_workspace_bytes(N, d, V, B.FLCE_DTYPE_BF16, 0) == 0
