@@ -24,7 +24,7 @@
  *     in the workspace (read it with flce_last_device_status).
  *   - The library never allocates device memory.  Scratch comes from the
  *     caller's `workspace` (size from flce_workspace_bytes; 256-byte aligned).
- *     The forward's is O(N + d) words plus one transposed copy of H; the
+ *     The forward's is O(N + d) words plus one pre-tiled copy of H; the
  *     backward's is copies of H, fp32 running sums of the outputs where a
  *     launch is chunked, and ONE staging tile for G of a capped size (see
  *     flce_workspace_bytes): a problem smaller than the cap stages its whole
@@ -105,7 +105,7 @@ const char* flce_status_string(flce_status s);
  * flce_backward (for_backward != 0) at this shape.  Returns 0 for an invalid
  * shape or dtype.  Host call, touches no device.
  *   forward : 12 * windows * Npad + 4 * ceil(V/1024) * d + 4 * N + O(N/256) bytes, plus Npad * d elements for the
- *             transposed copy of H (tuned bf16 loop).  Npad = N rounded up to 256.
+ *             pre-tiled copy of H that the tuned bf16 loop reads.  Npad = N rounded up to 256.
  *   backward: 2 * Npad * d elements (packed counted rows of H and their transpose) + 16 * Npad bytes
  *             + the staging tile for G: Nc x (Vc + 64) elements with Nc = min(Npad, 32768) and
  *               Vc = min(Vpad, 256 * vc) where vc = 128 tiles, or up to 512 when Nc < 8192 rows (so that
@@ -171,7 +171,7 @@ flce_status flce_backward(const void* H, const void* W, const int64_t* targets, 
  *   Limit    : shapes whose forward scratch exceeds the array return FLCE_ERR_WORKSPACE and launch nothing.
  *              The scratch is 12 * windows * ceil(N/256)*256 + 4 * ceil(V/1024) * d + 4 * N bytes + ~2 KiB
  *              (windows = max(4, ceil(256 / ceil(N/256))) unless FLCE_WINDOWS says otherwise): N up to about
- *              250 000 rows at d = 4096, V = 128256.  H is read in place (flce_forward's transposed copy of
+ *              250 000 rows at d = 4096, V = 128256.  H is read in place (flce_forward's pre-tiled copy of
  *              H is what does not fit a fixed array), which costs a few per cent of speed at large d.
  *   status_out, n_valid_out : device, one int32 / one int64, either may be NULL: the range flag (0 or
  *              FLCE_ERR_TARGET_RANGE) and the number of counted rows of THIS call, written on the stream
@@ -329,7 +329,7 @@ flce_status flce_profile_collect(double* ms_by_class, int64_t* launches_by_class
  * only with the nominal peak.  `workgroups` workgroups of 4 wavefronts each walk `tiles_per_workgroup` tiles
  * of 256 x 256 outputs over K = k_elems.
  *   mode 0 : the 32x32x16 bf16 MFMA back to back from registers (no memory traffic in the loop)
- *   mode 1 : the complete main loop, A K-contiguous and B read across memory rows (forward / recompute layout)
+ *   mode 1 : the complete main loop, A K-contiguous and B read across memory rows (the contractions' layouts)
  *   mode 2 : the complete main loop, both operands K-contiguous
  *   mode 3, 4 : modes 1, 2 with the matrix instructions left out (global -> LDS requests, LDS reads, waits and
  *            barriers only): the data path alone
@@ -344,6 +344,8 @@ flce_status flce_profile_collect(double* ms_by_class, int64_t* launches_by_class
  *            that each A tile is read once per launch, from HBM (the forward's access to W); in the other modes a
  *            group reads what its neighbour read one tile earlier
  *   mode 10 : mode 0 with the 16x16x32 bf16 MFMA (64 blocks of 4 accumulators per wavefront instead of 16 of 16)
+ *   mode 11 : the complete main loop, A K-contiguous and B pre-tiled, i.e. B's bytes taken as the 16 KiB LDS tile
+ *            images of its K steps one after the other (the forward / recompute layout: W and the pre-tiled copy of H)
  *   A  : device, bf16 [a_rows][k_elems];  B : device, bf16 [b_rows][k_elems];  BT : device, bf16 [k_elems][b_rows]
  *        (a_rows, b_rows multiples of 256, k_elems a multiple of 32); contents are the caller's choice of data.
  *   sink : device, workgroups * 256 floats, written once per thread.

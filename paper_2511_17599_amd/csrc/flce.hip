@@ -78,7 +78,7 @@ struct Plan {
   int64_t ld_v, ld_n;      // elements per row of the buffers whose rows run over a vocabulary / row chunk: the
                            // chunk's extent plus 64, so that rows never lie a power of two apart
   bool fast;               // tuned bf16 loop: W, Hc and G read in place by the contractions
-  bool hkr;                // forward / recompute read a transposed copy of H (needs its window within a descriptor's reach)
+  bool hkr;                // forward / recompute read a pre-tiled copy of H (tuned loop, unless the caller rules the copy out)
   int split_dh, split_dw;  // K slices of the dH / dW contraction launches (1 = unsplit)
   int64_t off_Hc, off_rowmap, off_tgt, off_lsec, off_gamc, off_HT, off_WT, off_G, off_GT, off_dHacc, off_dWacc, off_partial, bwd_bytes;
 };
@@ -170,7 +170,7 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p, bool all
   p.ld_v = vc_pad + 64;
   p.ld_n = nc_pad + 64;
   p.fast = fast_loop_ok(p, tn);
-  p.hkr = allow_h_copy && p.fast && window_ok(d, p.npad * 2);
+  p.hkr = allow_h_copy && p.fast;
   p.fwd_bytes = fwd_fixed + (p.hkr ? align_up(d * p.npad * p.esize, ALIGN) : 0);
   o = ALIGN;
   p.off_Hc = o;     o = align_up(o + d * p.npad * p.esize, ALIGN);
@@ -327,10 +327,10 @@ flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t
     if constexpr (L::TRANSPOSING) {
       T* HT = reinterpret_cast<T*>(ws + p.off_fHT);
       {
-        // H^T [d][npad], zero padded: the forward's second operand, read across memory rows
+        // the pre-tiled copy of H, zero padded to whole row blocks: the forward's second operand
         ProfScope ps(FLCE_PROF_FWD_EPILOGUE, st);
-        transpose_pad_kernel<U><<<dim3((unsigned)ceil_div(p.npad, 64), (unsigned)ceil_div(p.d, 64)), 256, 0, st>>>(
-            static_cast<const U*>(H), p.d, (int)p.N, 0, (int)p.d, reinterpret_cast<U*>(HT), p.npad, (int)p.npad);
+        pack_rows_kernel<<<dim3((unsigned)p.n_rb, (unsigned)ceil_div(p.d, 128)), 256, 0, st>>>(
+            static_cast<const char*>(H), (int)p.N, (int)p.d, reinterpret_cast<char*>(HT));
       }
       ProfScope ps(FLCE_PROF_FWD_TILES, st);
       fwd_tiles_kernel<T, L, true><<<grid, L::THREADS, L::LDS, st>>>(
@@ -398,12 +398,17 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     ProfScope ps(FLCE_PROF_BWD_PREP, st);
     compact_targets_kernel<<<1, 1024, 0, st>>>(y, N, V, slice.V_total, slice.v_begin, ignore_index, npad, rowmap,
                                                tgt_c, hdr);
-    // Hc (and Hc^T [d][npad]: the dW contraction's K-contiguous operand with the generic loop, the recompute's
-    // operand read across memory rows with the tuned loop), lse and Gamma per compact row, zero rows of dH
-    const bool need_t = !L::TRANSPOSING || p.hkr;
-    prep_rows_kernel<U><<<dim3((unsigned)(p.npad / 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
-        static_cast<const U*>(H), d, rowmap, reinterpret_cast<U*>(Hc), need_t ? reinterpret_cast<U*>(HT) : nullptr,
-        p.npad, lse, lse_c, rows.grad_rows, gam_c, y, N, slice.V_total, ignore_index, static_cast<U*>(dH));
+    // Hc, lse and Gamma per compact row, zero rows of dH; and a second copy of Hc: transposed [d][npad] with the
+    // generic loop (the dW contraction's K-contiguous operand), pre-tiled with the tuned loop (the recompute's)
+    if constexpr (L::TRANSPOSING)
+      prep_rows_packed_kernel<<<dim3((unsigned)p.n_rb, (unsigned)ceil_div(d, 128)), 256, 0, st>>>(
+          static_cast<const char*>(H), d, rowmap, reinterpret_cast<char*>(Hc),
+          p.hkr ? reinterpret_cast<char*>(HT) : nullptr, lse, lse_c, rows.grad_rows, gam_c, y, N, slice.V_total,
+          ignore_index, static_cast<char*>(dH));
+    else
+      prep_rows_kernel<U><<<dim3((unsigned)(p.npad / 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
+          static_cast<const U*>(H), d, rowmap, reinterpret_cast<U*>(Hc), reinterpret_cast<U*>(HT), p.npad, lse, lse_c,
+          rows.grad_rows, gam_c, y, N, slice.V_total, ignore_index, static_cast<U*>(dH));
   }
 
   bool hkr = false;
@@ -705,7 +710,7 @@ flce_status flce_backward(const void* H, const void* W, const int64_t* targets, 
 flce_status flce_forward_static(const void* H, const void* W, const int64_t* targets, int64_t N, int64_t d, int64_t V,
                                 int64_t ignore_index, flce_reduction reduction, flce_dtype dt, float* loss_out,
                                 float* lse_out, int32_t* status_out, int64_t* n_valid_out, void* hip_stream) {
-  // The plan without the transposed copy of H (its size grows with N*d): what is left of the forward
+  // The plan without the pre-tiled copy of H (its size grows with N*d): what is left of the forward
   // workspace is the per-window partials and per-block sums, O(N) words.
   if (!H || !W || !targets || !loss_out || !lse_out) return FLCE_ERR_BAD_ARG;
   if (reduction != FLCE_REDUCE_MEAN && reduction != FLCE_REDUCE_SUM) return FLCE_ERR_BAD_ARG;
@@ -857,7 +862,7 @@ flce_status flce_last_device_status(const void* workspace, void* hip_stream, int
 flce_status flce_probe(int mode, const void* A, const void* B, const void* BT, int64_t a_rows, int64_t b_rows,
                        int64_t k_elems, int workgroups, int tiles_per_workgroup, float* sink, void* hip_stream) {
   if (!A || !B || !BT || !sink) return FLCE_ERR_BAD_ARG;
-  if (mode < flce::PROBE_MFMA || mode > flce::PROBE_MFMA_16X16) return FLCE_ERR_BAD_ARG;
+  if (mode < flce::PROBE_MFMA || mode > flce::PROBE_LOOP_PK) return FLCE_ERR_BAD_ARG;
   if (a_rows <= 0 || b_rows <= 0 || (a_rows % flce::TILE) || (b_rows % flce::TILE) || k_elems < 32 || (k_elems % 32) ||
       workgroups <= 0 || tiles_per_workgroup <= 0)
     return FLCE_ERR_BAD_SHAPE;
@@ -884,6 +889,7 @@ flce_status flce_probe(int mode, const void* A, const void* B, const void* BT, i
     case flce::PROBE_HALF_KR_SOFTMAX: return launch(flce::probe_half_kernel<true>, flce::PROBE_HALF_LDS);
     case flce::PROBE_LOOP_KR_COLD: return launch(flce::probe_kernel<flce::PROBE_LOOP_KR_COLD>);
     case flce::PROBE_MFMA_16X16: return launch(flce::probe_mfma16_kernel<0>);
+    case flce::PROBE_LOOP_PK: return launch(flce::probe_kernel<flce::PROBE_LOOP_PK>);
   }
   return FLCE_ERR_BAD_ARG;
 }

@@ -6,10 +6,11 @@
 //             merge_rows_kernel + finalize_loss_kernel (the merging epilogue of
 //             Section 3.2.1, lse = m + ln a, per-row loss, fixed-order sums)
 //   backward: compact_targets_kernel + prep_rows_kernel (n_valid, range flag, and the
-//             rows that count packed together: ignored rows have a zero row of G; the
-//             packed rows also transposed for a main loop that reads that copy)
-//             transpose_pad_kernel (the forward's transposed copy of H; with the generic
-//             loop also the K-contiguous copy of W that the dH contraction needs)
+//             rows that count packed together: ignored rows have a zero row of G; a second
+//             copy of them transposed (generic loop) or pre-tiled (tuned loop))
+//             pack_rows_kernel (the forward's pre-tiled copy of H for the tuned loop);
+//             transpose_pad_kernel (generic loop: the K-contiguous copy of W that the dH
+//             contraction needs)
 //             recompute_kernel (Alg. 2: z recomputed, g = p - onehot, staged once in a
 //             fixed-size buffer; the generic loop also stages the transpose)
 //             contract_kernel (Eq. 4 and Eq. 5 as output-stationary MFMA
@@ -53,7 +54,7 @@ struct GenericLoop {      // any dtype, any K that is a multiple of 16 bytes; 8 
     TileSrc As, Bs;
     int k_bytes;
     __device__ __forceinline__ void start(const T* A, int64_t lda_bytes, int a_row0, int a_rows, const T* B, const T*,
-                                          int64_t ldb_bytes, int64_t, int b_row0, int b_rows, int k_elems, char*) {
+                                          int64_t ldb_bytes, int b_row0, int b_rows, int k_elems, char*) {
       As = TileSrc{reinterpret_cast<const char*>(A), lda_bytes, a_row0, a_rows};
       Bs = TileSrc{reinterpret_cast<const char*>(B), ldb_bytes, b_row0, b_rows};
       k_bytes = k_elems * (int)sizeof(T);
@@ -81,16 +82,18 @@ struct FastLoop {         // bf16, K a multiple of 32 elements; 4 wavefronts 2 x
   // block at a time where it uses them; left to itself the compiler copies most of a tile into vector
   // registers in one sweep at the end of the main loop, which overflows the register file into scratch memory.
   // A sequence of tiles with the same B operand: start() requests the first K stages of a tile (all LDS stages must
-  // be free: every wavefront is past the previous run()), run() computes it.  BT: B is given transposed, BT[k][n].
-  template <bool BT>
+  // be free: every wavefront is past the previous run()), run() computes it.  BP: B is also given pre-tiled (Bp:
+  // per 256-row block and K step the 16 KiB image of its LDS tile, see pack_rows_kernel), and that copy is read.
+  template <bool BP>
   struct Stream {
-    fast::Pipe<fast::KC, BT ? fast::KR : fast::KC> pipe;
+    fast::Pipe<fast::KC, BP ? fast::PK : fast::KC> pipe;
     __device__ __forceinline__ void start(const bf16_t* A, int64_t lda_bytes, int a_row0, int a_rows, const bf16_t* B,
-                                          const bf16_t* Bt, int64_t ldb_bytes, int64_t ldbt_bytes, int b_row0,
-                                          int b_rows, int k_elems, char* lds) {
+                                          const bf16_t* Bp, int64_t ldb_bytes, int b_row0, int b_rows, int k_elems,
+                                          char* lds) {
       const fast::Operand As{reinterpret_cast<const char*>(A), lda_bytes, a_row0, a_rows, 0};
-      if constexpr (BT) {
-        const fast::Operand Bs{reinterpret_cast<const char*>(Bt) + (int64_t)b_row0 * 2, ldbt_bytes, 0, k_elems, TILE * 2};
+      if constexpr (BP) {
+        // b_row0 is a multiple of 256: the block's images follow each other, one per K step
+        const fast::Operand Bs{reinterpret_cast<const char*>(Bp) + (int64_t)b_row0 * k_elems * 2, 0, 0, 0, 0};
         pipe.start(As, Bs, k_elems, lds);
       } else {
         const fast::Operand Bs{reinterpret_cast<const char*>(B), ldb_bytes, b_row0, b_rows, 0};
@@ -110,15 +113,6 @@ struct FastLoop {         // bf16, K a multiple of 32 elements; 4 wavefronts 2 x
     const fast::Operand As{static_cast<const char*>(A), lda_bytes, a_row0, a_rows, 0};
     const fast::Operand Bs{static_cast<const char*>(B), ldb_bytes, b_row0, b_rows, 0};
     fast::mainloop<fast::KC, fast::KC>(As, Bs, k_bytes / 2, lds, acc);
-  }
-  // Same contraction with B given transposed: BT[k][n] (K over memory rows, ldbt_bytes per row),
-  // tile columns b_col0 .. b_col0 + 255, all inside the padded row.
-  static __device__ __forceinline__ void run_bt(const void* A, int64_t lda_bytes, int a_row0, int a_rows,
-                                                const void* BT, int64_t ldbt_bytes, int b_col0, int k_elems,
-                                                char* lds, f32x16 (&acc)[WM][WN]) {
-    const fast::Operand As{static_cast<const char*>(A), lda_bytes, a_row0, a_rows, 0};
-    const fast::Operand Bs{static_cast<const char*>(BT) + (int64_t)b_col0 * 2, ldbt_bytes, 0, k_elems, TILE * 2};
-    fast::mainloop<fast::KC, fast::KR>(As, Bs, k_elems, lds, acc);
   }
 };
 
@@ -204,9 +198,9 @@ __device__ __forceinline__ void merge_fixed(const float (&m)[S], const float (&a
 // (m, a, z_target) in registers across the vocabulary tiles of its window.
 // part = [3][n_win][n_rb * 256] floats: m, a, z_target per (window, row).
 // ------------------------------------------------------------------------------------
-// HKR: the hidden states are also given transposed, HT[d][n_rb * 256] (zero padded), and the main
-// loop reads that copy (an operand whose K index runs over memory rows is fetched in 512-byte
-// runs and measures faster than two K-contiguous operands).
+// HKR: the hidden states are also given pre-tiled (HT: pack_rows_kernel's copy, zero padded to whole row
+// blocks), and the main loop reads that copy: every global -> LDS request is then 1 KiB of consecutive
+// bytes, where the rows of H themselves give it 64 bytes at a time.
 template <typename T, typename L, bool HKR>
 __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
     const T* __restrict__ H, const T* __restrict__ HT, const T* __restrict__ W, const int64_t* __restrict__ y,
@@ -236,11 +230,11 @@ __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
   // The tuned loop's first K stages of tile t+1 are requested before the softmax update of tile t (which touches
   // no memory), so the update hides their latency: it matters when the K loop is short (small d).
   typename L::template Stream<HKR> stream;
-  if (vt_begin < vt_end) stream.start(W, ld_bytes, vt_begin * TILE, V, H, HT, ld_bytes, (int64_t)n_rb * TILE * sizeof(T), n0, N, d, lds);
+  if (vt_begin < vt_end) stream.start(W, ld_bytes, vt_begin * TILE, V, H, HT, ld_bytes, n0, N, d, lds);
   for (int vt = vt_begin; vt < vt_end; ++vt) {
     const int v0 = vt * TILE;
     stream.run(lds, acc);
-    if (vt + 1 < vt_end) stream.start(W, ld_bytes, v0 + TILE, V, H, HT, ld_bytes, (int64_t)n_rb * TILE * sizeof(T), n0, N, d, lds);
+    if (vt + 1 < vt_end) stream.start(W, ld_bytes, v0 + TILE, V, H, HT, ld_bytes, n0, N, d, lds);
 
     // Online update of (m, a) and the target gather, one 32 x 32 accumulator block at a time
     // (16 logits of one token per lane).  All 32 rows of a block belong to one wavefront, so
@@ -600,6 +594,82 @@ __global__ __launch_bounds__(256) void prep_rows_kernel(const U* __restrict__ H,
   }
 }
 
+// The pre-tiled copy of a row-major bf16 matrix X[rows][d] (d a multiple of 32) that the tuned main loop reads as
+// its B operand: for every block of 256 rows and every K step of 32 elements, the 16 KiB image of that step's LDS
+// tile, images of one row block following each other in K order:
+//   P[(rb * d / 32 + kt) * 16 KiB + r * 64 + 16 * pos] = the 16 bytes X[rb * 256 + r][kt * 32 + 8 * (pos ^ (r / 4) % 4) ...]
+// (the main loop's K-contiguous LDS tile, 256 rows of 64 bytes with its chunk swizzle), rows past the end as zeros.
+// pack_rows_store: one thread's part, the 64 bytes of row r at K step kt.
+__device__ __forceinline__ void pack_rows_store(const u32x4 (&chunk)[4], char* __restrict__ P, int64_t image, int r) {
+  u32x4* dst = reinterpret_cast<u32x4*>(P + image * fast::OPER + r * 64);
+  const int sw = (r >> 2) & 3;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) dst[c ^ sw] = chunk[c];
+}
+
+// grid (row blocks, ceil(d / 128)), 256 threads: thread r copies 256 bytes (4 K steps) of row rb * 256 + r.
+__global__ __launch_bounds__(256) void pack_rows_kernel(const char* __restrict__ X, int rows, int d,
+                                                        char* __restrict__ P) {
+  const int rb = blockIdx.x, r = threadIdx.x, row = rb * TILE + r;
+  const int KT = d / fast::BK;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const int kt = blockIdx.y * 4 + kk;
+    if (kt >= KT) break;
+    u32x4 chunk[4];
+    const u32x4* src = reinterpret_cast<const u32x4*>(X + ((int64_t)row * d + kt * fast::BK) * 2);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) chunk[c] = u32x4{0u, 0u, 0u, 0u};
+    if (row < rows) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) chunk[c] = src[c];
+    }
+    pack_rows_store(chunk, P, (int64_t)rb * KT + kt, r);
+  }
+}
+
+// The backward's row preparation for the tuned loop, one launch (same grid as pack_rows_kernel over the padded
+// compact rows): Hc[c][:] = H[rowmap[c]][:] (zero behind the last counted row), HcP = its pre-tiled copy (when the
+// main loop reads one), lse_c / gam_c gathered likewise, dH rows of tokens that do not count set to exactly +0.
+__global__ __launch_bounds__(256) void prep_rows_packed_kernel(const char* __restrict__ H, int d,
+                                                               const int* __restrict__ rowmap, char* __restrict__ Hc,
+                                                               char* __restrict__ HcP, const float* __restrict__ lse,
+                                                               float* __restrict__ lse_c,
+                                                               const float* __restrict__ grad_rows,
+                                                               float* __restrict__ gam_c,
+                                                               const int64_t* __restrict__ y, int N, int64_t V_total,
+                                                               int64_t ignore_index, char* __restrict__ dH) {
+  const int rb = blockIdx.x, r = threadIdx.x, c = rb * TILE + r;   // compact row c, and also token c of the original order
+  const int KT = d / fast::BK;
+  const int n = rowmap[c];
+  bool oor;
+  const bool dead = c < N && !target_counts(y[c], ignore_index, V_total, oor);
+  if (blockIdx.y == 0) {
+    lse_c[c] = (n >= 0) ? lse[n] : 0.f;
+    if (grad_rows) gam_c[c] = (n >= 0) ? grad_rows[n] : 0.f;
+  }
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const int kt = blockIdx.y * 4 + kk;
+    if (kt >= KT) break;
+    u32x4 chunk[4];
+    const int64_t col_bytes = (int64_t)kt * fast::BK * 2;
+    const u32x4* src = reinterpret_cast<const u32x4*>(H + (int64_t)(n < 0 ? 0 : n) * d * 2 + col_bytes);
+    u32x4* plain = reinterpret_cast<u32x4*>(Hc + (int64_t)c * d * 2 + col_bytes);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      chunk[q] = n >= 0 ? src[q] : u32x4{0u, 0u, 0u, 0u};
+      plain[q] = chunk[q];
+    }
+    if (HcP) pack_rows_store(chunk, HcP, (int64_t)rb * KT + kt, r);
+    if (dead) {
+      u32x4* z = reinterpret_cast<u32x4*>(dH + (int64_t)c * d * 2 + col_bytes);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) z[q] = u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+}
+
 // dst[c][r] = src[r0 + r][c]  for c < cols, r < rows_pad; zero where r0 + r >= rows_total.
 // U is an unsigned integer type of the element's width (pure data movement).
 template <typename U>
@@ -700,8 +770,7 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
   place(t, p, q);
   RowMeta<L> meta;
   if constexpr (L::TRANSPOSING) load_meta((a.nt0 + p) * TILE, meta);
-  stream.start(W, ld_bytes, (a.vt0 + q) * TILE, V, Hc, HcT, ld_bytes, (int64_t)npad * sizeof(T), (a.nt0 + p) * TILE, npad, d,
-               lds);
+  stream.start(W, ld_bytes, (a.vt0 + q) * TILE, V, Hc, HcT, ld_bytes, (a.nt0 + p) * TILE, npad, d, lds);
   f32x16 acc[L::WM][L::WN];
   for (;;) {
     stream.run(lds, acc);
@@ -715,8 +784,7 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
     if (more) {
       place(t_next, p_next, q_next);
       load_meta((a.nt0 + p_next) * TILE, meta_next);
-      stream.start(W, ld_bytes, (a.vt0 + q_next) * TILE, V, Hc, HcT, ld_bytes, (int64_t)npad * sizeof(T),
-                   (a.nt0 + p_next) * TILE, npad, d, lds);
+      stream.start(W, ld_bytes, (a.vt0 + q_next) * TILE, V, Hc, HcT, ld_bytes, (a.nt0 + p_next) * TILE, npad, d, lds);
     }
 
     const int v0 = (a.vt0 + q) * TILE;

@@ -16,6 +16,12 @@
 //           lane gets back 4 consecutive K values of one tile row).
 //     This lets dH = G.W and dW = G^T.H read G, W and H where they are, with no
 //     transposed copies.
+//       PK ("packed"): the operand has been copied into the order of its LDS tiles beforehand:
+//           per 256-row block and K step one 16 KiB image of the KC tile (swizzle included),
+//           images of a block one after the other.  Every request is then 1 KiB of consecutive
+//           bytes (KC: 16 pieces of 64 bytes) and the fragments are KC's.  Worth a copy for an
+//           operand that is small and read many times (the hidden states in the forward and the
+//           recompute: +2 % on the whole loop).
 //   * LDS swizzles (applied on the global side, because the DMA writes LDS linearly):
 //     KC: 16-byte chunk index ^ (row / 4) % 4; KR: 64-byte chunk index ^ (k % 4).  Both
 //     spread what one LDS instruction touches in a cycle over all 64 banks.
@@ -48,7 +54,7 @@ constexpr int OPER = TILE * BK * 2;       // 16 KiB per operand per stage (eithe
 constexpr int STAGE = 2 * OPER;
 constexpr int LDS_BYTES = NS * STAGE;     // 128 KiB with 4 stages
 
-enum : int { KC = 0, KR = 1 };
+enum : int { KC = 0, KR = 1, PK = 2 };
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -88,7 +94,9 @@ template <int LAYOUT, int TILE_ROWS = TILE>
 __device__ __forceinline__ u32x4 make_rsrc(const Operand& s, int k_elems) {
   uint32_t n = 0;
   const char* b = s.base;
-  if (LAYOUT == KC) {
+  if (LAYOUT == PK) {
+    n = (uint32_t)(k_elems / BK) * OPER;
+  } else if (LAYOUT == KC) {
     int vr = min(TILE_ROWS, s.rows - s.row0);
     if (vr > 0) n = (uint32_t)((int64_t)(vr - 1) * s.ld_bytes + k_elems * 2);
     b += (int64_t)s.row0 * s.ld_bytes;
@@ -139,7 +147,9 @@ struct Loader {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
     for (int i = 0; i < REQS; ++i) {
-      if (LAYOUT == KC) {
+      if (LAYOUT == PK) {
+        v[i] = (uint32_t)(wave * 4096 + i * 1024 + lane * 16);
+      } else if (LAYOUT == KC) {
         const int row = wave * (16 * REQS) + i * 16 + (lane >> 2);
         const int chunk = (lane & 3) ^ ((row >> 2) & 3);
         v[i] = (uint32_t)(row * s.ld_bytes) + chunk * 16;
@@ -149,11 +159,11 @@ struct Loader {
         v[i] = (uint32_t)(krow * s.ld_bytes) + off;
       }
     }
-    k_step = LAYOUT == KC ? BK * 2 : (uint32_t)(BK * s.ld_bytes);
+    k_step = LAYOUT == PK ? OPER : LAYOUT == KC ? BK * 2 : (uint32_t)(BK * s.ld_bytes);
   }
   // request i of K tile kt into `dst` (this wavefront's slice of the operand tile of some stage)
   __device__ __forceinline__ void issue(int i, char* dst, int kt) const {
-    if (LAYOUT == KC)
+    if (LAYOUT != KR)
       dma16(rs, lds_address(dst + i * 1024), v[i], (uint32_t)kt * k_step);
     else   // the K advance moves to other rows: keep it in the per-lane offset, which the range check covers
       dma16(rs, lds_address(dst + i * 1024), v[i] + (uint32_t)kt * k_step, 0);
@@ -168,7 +178,7 @@ struct FragAddr {
   int o[4];   // KC: o[ks] for the two MFMA K steps (o[2], o[3] unused); KR: o[i] for the 4 blocks
   __device__ __forceinline__ void init(int wsub) {
     const int lane = threadIdx.x & 63;
-    if (LAYOUT == KC) {
+    if (LAYOUT != KR) {
       const int l32 = lane & 31, half = lane >> 5, sw = (l32 >> 2) & 3;
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) o[ks] = (wsub * 32 * BLOCKS + l32) * 64 + (((ks * 2 + half) ^ sw) << 4);
@@ -179,7 +189,7 @@ struct FragAddr {
       for (int i = 0; i < 4; ++i) o[i] = (8 * kh + e) * 512 + wsub * 256 + 64 * (i ^ e) + 32 * mg + 8 * q;
     }
   }
-  static constexpr int READS = LAYOUT == KC ? BLOCKS : 8;   // LDS reads per MFMA K step
+  static constexpr int READS = LAYOUT != KR ? BLOCKS : 8;   // LDS reads per MFMA K step
 };
 
 struct Frags {
@@ -189,7 +199,7 @@ struct Frags {
 // Read number t (0 .. READS-1) of the fragments of one operand for MFMA K step ks of a stage.
 template <int LAYOUT, int BLOCKS>
 __device__ __forceinline__ void read_frag(bf16x8 (&f)[4], const FragAddr<LAYOUT, BLOCKS>& fa, const char* tile, int ks, int t) {
-  if (LAYOUT == KC) {
+  if (LAYOUT != KR) {
     f[t] = *reinterpret_cast<const bf16x8*>(tile + fa.o[ks] + t * 32 * 64);
   } else {
     const int i = t >> 1, r = t & 1;

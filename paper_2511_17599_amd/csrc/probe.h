@@ -3,8 +3,10 @@
 // rather than against the nominal peak only.  One workgroup per CU-sized slot, 4 wavefronts, as in the real kernels.
 //   PROBE_MFMA     : the 32x32x16 bf16 MFMA issued back to back from registers (fragments loaded once): the rate
 //                    the matrix pipe sustains under the chip's power limit with this data.
-//   PROBE_LOOP_KR  : the complete main loop of the forward / recompute (A K-contiguous, B read across memory rows),
+//   PROBE_LOOP_KR  : the complete main loop with A K-contiguous and B read across memory rows,
 //                    tile after tile with no post-processing of the accumulators.
+//   PROBE_LOOP_PK  : the same with B pre-tiled (its bytes taken as the LDS tile images of its K steps, whatever they
+//                    hold): the main loop of the forward / recompute.
 //   PROBE_LOOP_KC  : the same with both operands K-contiguous.
 //   PROBE_DATA_KR / PROBE_DATA_KC : those loops with the matrix instructions left out (global -> LDS requests, LDS
 //                    fragment reads, waits, barriers only): the data path alone.
@@ -34,7 +36,7 @@ namespace flce {
 
 enum : int {
   PROBE_MFMA = 0, PROBE_LOOP_KR = 1, PROBE_LOOP_KC = 2, PROBE_DATA_KR = 3, PROBE_DATA_KC = 4, PROBE_FREE_RUN = 5,
-  PROBE_LOOP_KR_SOFTMAX = 6, PROBE_HALF_KR = 7, PROBE_HALF_KR_SOFTMAX = 8, PROBE_LOOP_KR_COLD = 9, PROBE_MFMA_16X16 = 10
+  PROBE_LOOP_KR_SOFTMAX = 6, PROBE_HALF_KR = 7, PROBE_HALF_KR_SOFTMAX = 8, PROBE_LOOP_KR_COLD = 9, PROBE_MFMA_16X16 = 10, PROBE_LOOP_PK = 11
 };
 
 struct ProbeArgs {
@@ -243,8 +245,9 @@ __global__ __launch_bounds__(fast::THREADS) void probe_kernel(ProbeArgs p) {
     fast::wait_vm_and_lds<0>();
     __builtin_amdgcn_s_barrier();
   } else {
-    constexpr int LB = (MODE == PROBE_LOOP_KR || MODE == PROBE_DATA_KR || MODE == PROBE_LOOP_KR_SOFTMAX || MODE == PROBE_LOOP_KR_COLD) ? fast::KR : fast::KC;
-    constexpr bool MF = MODE == PROBE_LOOP_KR || MODE == PROBE_LOOP_KC || MODE == PROBE_LOOP_KR_SOFTMAX || MODE == PROBE_LOOP_KR_COLD;
+    constexpr int LB = (MODE == PROBE_LOOP_KR || MODE == PROBE_DATA_KR || MODE == PROBE_LOOP_KR_SOFTMAX || MODE == PROBE_LOOP_KR_COLD) ? fast::KR
+                       : MODE == PROBE_LOOP_PK ? fast::PK : fast::KC;
+    constexpr bool MF = MODE == PROBE_LOOP_KR || MODE == PROBE_LOOP_KC || MODE == PROBE_LOOP_KR_SOFTMAX || MODE == PROBE_LOOP_KR_COLD || MODE == PROBE_LOOP_PK;
     fast::Pipe<fast::KC, LB, MF> pipe;
     const int64_t ld = (int64_t)p.k_elems * 2;
     for (int t = 0; t < p.tiles_per_wg; ++t) {
@@ -254,6 +257,10 @@ __global__ __launch_bounds__(fast::THREADS) void probe_kernel(ProbeArgs p) {
       if constexpr (LB == fast::KR) {
         const fast::Operand Bs{reinterpret_cast<const char*>(p.BT) + (int64_t)b0 * 2, (int64_t)p.b_rows * 2, 0,
                                p.k_elems, TILE * 2};
+        pipe.start(As, Bs, p.k_elems, lds);
+      } else if constexpr (LB == fast::PK) {
+        // the B tile's bytes taken as a pre-tiled image: K tile kt of the tile is the 16 KiB at kt * 16 KiB
+        const fast::Operand Bs{reinterpret_cast<const char*>(p.B) + (int64_t)b0 * ld, 0, 0, 0, 0};
         pipe.start(As, Bs, p.k_elems, lds);
       } else {
         const fast::Operand Bs{reinterpret_cast<const char*>(p.B), ld, b0, p.b_rows, 0};
