@@ -329,7 +329,7 @@ flce_status forward_t(const Plan& p, const void* H, const void* W, const int64_t
       {
         // the pre-tiled copy of H, zero padded to whole row blocks: the forward's second operand
         ProfScope ps(FLCE_PROF_FWD_EPILOGUE, st);
-        pack_rows_kernel<<<dim3((unsigned)p.n_rb, (unsigned)ceil_div(p.d, 128)), 256, 0, st>>>(
+        pack_rows_kernel<<<dim3((unsigned)(p.npad / 64), (unsigned)ceil_div(p.d, 128)), 256, 0, st>>>(
             static_cast<const char*>(H), (int)p.N, (int)p.d, reinterpret_cast<char*>(HT));
       }
       ProfScope ps(FLCE_PROF_FWD_TILES, st);
@@ -401,7 +401,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     // Hc, lse and Gamma per compact row, zero rows of dH; and a second copy of Hc: transposed [d][npad] with the
     // generic loop (the dW contraction's K-contiguous operand), pre-tiled with the tuned loop (the recompute's)
     if constexpr (L::TRANSPOSING)
-      prep_rows_packed_kernel<<<dim3((unsigned)p.n_rb, (unsigned)ceil_div(d, 128)), 256, 0, st>>>(
+      prep_rows_packed_kernel<<<dim3((unsigned)(p.npad / 64), (unsigned)ceil_div(d, 128)), 256, 0, st>>>(
           static_cast<const char*>(H), d, rowmap, reinterpret_cast<char*>(Hc),
           p.hkr ? reinterpret_cast<char*>(HT) : nullptr, lse, lse_c, rows.grad_rows, gam_c, y, N, slice.V_total,
           ignore_index, static_cast<char*>(dH));

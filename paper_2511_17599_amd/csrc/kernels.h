@@ -607,30 +607,28 @@ __device__ __forceinline__ void pack_rows_store(const u32x4 (&chunk)[4], char* _
   for (int c = 0; c < 4; ++c) dst[c ^ sw] = chunk[c];
 }
 
-// grid (row blocks, ceil(d / 128)), 256 threads: thread r copies 256 bytes (4 K steps) of row rb * 256 + r.
+// grid (rows_pad / 64, ceil(d / 128)), 256 threads: thread t copies the 64 bytes of row 64 * blockIdx.x + t / 4 at
+// K step 4 * blockIdx.y + t % 4, so that a wavefront reads 16 rows x 256 consecutive bytes and writes 1 KiB runs.
 __global__ __launch_bounds__(256) void pack_rows_kernel(const char* __restrict__ X, int rows, int d,
                                                         char* __restrict__ P) {
-  const int rb = blockIdx.x, r = threadIdx.x, row = rb * TILE + r;
+  const int row = blockIdx.x * 64 + (threadIdx.x >> 2), kt = blockIdx.y * 4 + (threadIdx.x & 3);
   const int KT = d / fast::BK;
+  if (kt >= KT) return;
+  u32x4 chunk[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    const int kt = blockIdx.y * 4 + kk;
-    if (kt >= KT) break;
-    u32x4 chunk[4];
+  for (int c = 0; c < 4; ++c) chunk[c] = u32x4{0u, 0u, 0u, 0u};
+  if (row < rows) {
     const u32x4* src = reinterpret_cast<const u32x4*>(X + ((int64_t)row * d + kt * fast::BK) * 2);
 #pragma unroll
-    for (int c = 0; c < 4; ++c) chunk[c] = u32x4{0u, 0u, 0u, 0u};
-    if (row < rows) {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) chunk[c] = src[c];
-    }
-    pack_rows_store(chunk, P, (int64_t)rb * KT + kt, r);
+    for (int c = 0; c < 4; ++c) chunk[c] = src[c];
   }
+  pack_rows_store(chunk, P, (int64_t)(row / TILE) * KT + kt, row % TILE);
 }
 
-// The backward's row preparation for the tuned loop, one launch (same grid as pack_rows_kernel over the padded
-// compact rows): Hc[c][:] = H[rowmap[c]][:] (zero behind the last counted row), HcP = its pre-tiled copy (when the
-// main loop reads one), lse_c / gam_c gathered likewise, dH rows of tokens that do not count set to exactly +0.
+// The backward's row preparation for the tuned loop, one launch (same grid and thread mapping as pack_rows_kernel,
+// over the padded compact rows): Hc[c][:] = H[rowmap[c]][:] (zero behind the last counted row), HcP = its pre-tiled
+// copy (when the main loop reads one), lse_c / gam_c gathered likewise, dH rows of tokens that do not count set to
+// exactly +0.
 __global__ __launch_bounds__(256) void prep_rows_packed_kernel(const char* __restrict__ H, int d,
                                                                const int* __restrict__ rowmap, char* __restrict__ Hc,
                                                                char* __restrict__ HcP, const float* __restrict__ lse,
@@ -639,34 +637,34 @@ __global__ __launch_bounds__(256) void prep_rows_packed_kernel(const char* __res
                                                                float* __restrict__ gam_c,
                                                                const int64_t* __restrict__ y, int N, int64_t V_total,
                                                                int64_t ignore_index, char* __restrict__ dH) {
-  const int rb = blockIdx.x, r = threadIdx.x, c = rb * TILE + r;   // compact row c, and also token c of the original order
+  const int c = blockIdx.x * 64 + (threadIdx.x >> 2);     // compact row c, and also token c of the original order
+  const int kt = blockIdx.y * 4 + (threadIdx.x & 3);
   const int KT = d / fast::BK;
   const int n = rowmap[c];
-  bool oor;
-  const bool dead = c < N && !target_counts(y[c], ignore_index, V_total, oor);
-  if (blockIdx.y == 0) {
+  if (blockIdx.y == 0 && (threadIdx.x & 3) == 0) {
     lse_c[c] = (n >= 0) ? lse[n] : 0.f;
     if (grad_rows) gam_c[c] = (n >= 0) ? grad_rows[n] : 0.f;
   }
+  if (kt >= KT) return;
+  bool oor;
+  const bool dead = c < N && !target_counts(y[c], ignore_index, V_total, oor);
+  const int64_t col_bytes = (int64_t)kt * fast::BK * 2;
+  u32x4 chunk[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    const int kt = blockIdx.y * 4 + kk;
-    if (kt >= KT) break;
-    u32x4 chunk[4];
-    const int64_t col_bytes = (int64_t)kt * fast::BK * 2;
-    const u32x4* src = reinterpret_cast<const u32x4*>(H + (int64_t)(n < 0 ? 0 : n) * d * 2 + col_bytes);
-    u32x4* plain = reinterpret_cast<u32x4*>(Hc + (int64_t)c * d * 2 + col_bytes);
+  for (int q = 0; q < 4; ++q) chunk[q] = u32x4{0u, 0u, 0u, 0u};
+  if (n >= 0) {
+    const u32x4* src = reinterpret_cast<const u32x4*>(H + (int64_t)n * d * 2 + col_bytes);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      chunk[q] = n >= 0 ? src[q] : u32x4{0u, 0u, 0u, 0u};
-      plain[q] = chunk[q];
-    }
-    if (HcP) pack_rows_store(chunk, HcP, (int64_t)rb * KT + kt, r);
-    if (dead) {
-      u32x4* z = reinterpret_cast<u32x4*>(dH + (int64_t)c * d * 2 + col_bytes);
+    for (int q = 0; q < 4; ++q) chunk[q] = src[q];
+  }
+  u32x4* plain = reinterpret_cast<u32x4*>(Hc + (int64_t)c * d * 2 + col_bytes);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) z[q] = u32x4{0u, 0u, 0u, 0u};
-    }
+  for (int q = 0; q < 4; ++q) plain[q] = chunk[q];
+  if (HcP) pack_rows_store(chunk, HcP, (int64_t)(c / TILE) * KT + kt, c % TILE);
+  if (dead) {
+    u32x4* z = reinterpret_cast<u32x4*>(dH + (int64_t)c * d * 2 + col_bytes);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) z[q] = u32x4{0u, 0u, 0u, 0u};
   }
 }
 
