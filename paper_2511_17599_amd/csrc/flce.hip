@@ -171,7 +171,7 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p, bool all
   p.ld_n = nc_pad + 64;
   p.fast = fast_loop_ok(p, tn);
   p.hkr = allow_h_copy && p.fast;
-  p.fwd_bytes = fwd_fixed + (p.hkr ? align_up(d * p.npad * p.esize, ALIGN) : 0);
+  p.fwd_bytes = fwd_fixed + (p.hkr ? align_up(packed_block_offset(p.n_rb, (int)d), ALIGN) : 0);
   o = ALIGN;
   p.off_Hc = o;     o = align_up(o + d * p.npad * p.esize, ALIGN);
   p.off_rowmap = o; o = align_up(o + p.npad * 4, ALIGN);
@@ -180,7 +180,8 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p, bool all
   p.off_gamc = o;   o = align_up(o + p.npad * 4, ALIGN);
   p.off_G = o;      o = align_up(o + nc_pad * p.ld_v * p.esize, ALIGN);
   // K-contiguous copies, only for main loops that cannot read an operand across memory rows
-  p.off_HT = o;     if (!p.fast || p.hkr) o = align_up(o + d * p.npad * p.esize, ALIGN);
+  p.off_HT = o;     if (!p.fast) o = align_up(o + d * p.npad * p.esize, ALIGN);
+                    else if (p.hkr) o = align_up(o + packed_block_offset(p.n_rb, (int)d), ALIGN);
   p.off_WT = o;     if (!p.fast) o = align_up(o + d * p.ld_v * p.esize, ALIGN);
   p.off_GT = o;     if (!p.fast) o = align_up(o + vc_pad * p.ld_n * p.esize, ALIGN);
   p.off_dHacc = o;  if (p.n_vch > 1) o = align_up(o + N * d * 4, ALIGN);

@@ -31,6 +31,16 @@
 
 namespace flce {
 
+// Byte offset of row block rb in a pre-tiled copy of a matrix with d columns: the block's d / 32 images of 16 KiB
+// plus a skew, so that the blocks do not start a power of two apart (the workgroups resident at one time stream
+// several dozen blocks side by side, and blocks exactly 2^k bytes apart land on the same DRAM banks).
+#ifndef FLCE_PACK_SKEW
+#define FLCE_PACK_SKEW 17408
+#endif
+__host__ __device__ __forceinline__ int64_t packed_block_offset(int rb, int d) {
+  return (int64_t)rb * ((int64_t)d * (TILE * 2) + FLCE_PACK_SKEW);
+}
+
 // Main-loop policies.  A kernel is written once against this interface:
 //   THREADS, WM x WN (32x32 accumulator blocks per wavefront), LDS (dynamic LDS bytes),
 //   tile_m(i, r) / tile_n(j): position of acc[i][j][r] inside the 256 x 256 tile,
@@ -93,7 +103,7 @@ struct FastLoop {         // bf16, K a multiple of 32 elements; 4 wavefronts 2 x
       const fast::Operand As{reinterpret_cast<const char*>(A), lda_bytes, a_row0, a_rows, 0};
       if constexpr (BP) {
         // b_row0 is a multiple of 256: the block's images follow each other, one per K step
-        const fast::Operand Bs{reinterpret_cast<const char*>(Bp) + (int64_t)b_row0 * k_elems * 2, 0, 0, 0, 0};
+        const fast::Operand Bs{reinterpret_cast<const char*>(Bp) + packed_block_offset(b_row0 / TILE, k_elems), 0, 0, 0, 0};
         pipe.start(As, Bs, k_elems, lds);
       } else {
         const fast::Operand Bs{reinterpret_cast<const char*>(B), ldb_bytes, b_row0, b_rows, 0};
@@ -599,9 +609,9 @@ __global__ __launch_bounds__(256) void prep_rows_kernel(const U* __restrict__ H,
 // tile, images of one row block following each other in K order:
 //   P[(rb * d / 32 + kt) * 16 KiB + r * 64 + 16 * pos] = the 16 bytes X[rb * 256 + r][kt * 32 + 8 * (pos ^ (r / 4) % 4) ...]
 // (the main loop's K-contiguous LDS tile, 256 rows of 64 bytes with its chunk swizzle), rows past the end as zeros.
-// pack_rows_store: one thread's part, the 64 bytes of row r at K step kt.
-__device__ __forceinline__ void pack_rows_store(const u32x4 (&chunk)[4], char* __restrict__ P, int64_t image, int r) {
-  u32x4* dst = reinterpret_cast<u32x4*>(P + image * fast::OPER + r * 64);
+// pack_rows_store: one thread's part, the 64 bytes of row r of row block rb at K step kt.
+__device__ __forceinline__ void pack_rows_store(const u32x4 (&chunk)[4], char* __restrict__ P, int rb, int kt, int d, int r) {
+  u32x4* dst = reinterpret_cast<u32x4*>(P + packed_block_offset(rb, d) + (int64_t)kt * fast::OPER + r * 64);
   const int sw = (r >> 2) & 3;
 #pragma unroll
   for (int c = 0; c < 4; ++c) dst[c ^ sw] = chunk[c];
@@ -622,7 +632,7 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(const char* __restrict__
 #pragma unroll
     for (int c = 0; c < 4; ++c) chunk[c] = src[c];
   }
-  pack_rows_store(chunk, P, (int64_t)(row / TILE) * KT + kt, row % TILE);
+  pack_rows_store(chunk, P, row / TILE, kt, d, row % TILE);
 }
 
 // The backward's row preparation for the tuned loop, one launch (same grid and thread mapping as pack_rows_kernel,
@@ -660,7 +670,7 @@ __global__ __launch_bounds__(256) void prep_rows_packed_kernel(const char* __res
   u32x4* plain = reinterpret_cast<u32x4*>(Hc + (int64_t)c * d * 2 + col_bytes);
 #pragma unroll
   for (int q = 0; q < 4; ++q) plain[q] = chunk[q];
-  if (HcP) pack_rows_store(chunk, HcP, (int64_t)(c / TILE) * KT + kt, c % TILE);
+  if (HcP) pack_rows_store(chunk, HcP, c / TILE, kt, d, c % TILE);
   if (dead) {
     u32x4* z = reinterpret_cast<u32x4*>(dH + (int64_t)c * d * 2 + col_bytes);
 #pragma unroll
