@@ -346,6 +346,9 @@ flce_status flce_profile_collect(double* ms_by_class, int64_t* launches_by_class
  *   mode 10 : mode 0 with the 16x16x32 bf16 MFMA (64 blocks of 4 accumulators per wavefront instead of 16 of 16)
  *   mode 11 : the complete main loop, A K-contiguous and B pre-tiled, i.e. B's bytes taken as the 16 KiB LDS tile
  *            images of its K steps one after the other (the forward / recompute layout: W and the pre-tiled copy of H)
+ *   mode 12 .. 16 : the complete main loop for the operand layout pairs (A / B) rows / rows (the dW contraction),
+ *            pre-tiled / rows, rows / K-contiguous (the dH contraction), rows / pre-tiled, pre-tiled / pre-tiled;
+ *            "rows" = read across memory rows.  Timing only: the operands' bytes are taken from the buffers as they are.
  *   A  : device, bf16 [a_rows][k_elems];  B : device, bf16 [b_rows][k_elems];  BT : device, bf16 [k_elems][b_rows]
  *        (a_rows, b_rows multiples of 256, k_elems a multiple of 32); contents are the caller's choice of data.
  *   sink : device, workgroups * 256 floats, written once per thread.

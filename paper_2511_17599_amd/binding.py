@@ -231,7 +231,8 @@ def flce_profile_collect():
 
 
 PROBE_MODES = ("mfma_only", "loop_kc_kr", "loop_kc_kc", "data_kc_kr", "data_kc_kc", "free_run_kc_kr",
-               "loop_kc_kr_softmax", "half_kc_kr", "half_kc_kr_softmax", "loop_kc_kr_cold", "mfma_16x16x32_only", "loop_kc_packed")
+               "loop_kc_kr_softmax", "half_kc_kr", "half_kc_kr_softmax", "loop_kc_kr_cold", "mfma_16x16x32_only", "loop_kc_packed",
+               "loop_kr_kr", "loop_packed_kr", "loop_kr_kc", "loop_kr_packed", "loop_packed_packed")
 
 
 def flce_probe(mode, A, B, BT, a_rows, b_rows, k_elems, workgroups, tiles_per_workgroup, sink, hip_stream=None):

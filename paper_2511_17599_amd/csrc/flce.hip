@@ -863,7 +863,7 @@ flce_status flce_last_device_status(const void* workspace, void* hip_stream, int
 flce_status flce_probe(int mode, const void* A, const void* B, const void* BT, int64_t a_rows, int64_t b_rows,
                        int64_t k_elems, int workgroups, int tiles_per_workgroup, float* sink, void* hip_stream) {
   if (!A || !B || !BT || !sink) return FLCE_ERR_BAD_ARG;
-  if (mode < flce::PROBE_MFMA || mode > flce::PROBE_LOOP_PK) return FLCE_ERR_BAD_ARG;
+  if (mode < flce::PROBE_MFMA || mode > flce::PROBE_PAIR_PK_PK) return FLCE_ERR_BAD_ARG;
   if (a_rows <= 0 || b_rows <= 0 || (a_rows % flce::TILE) || (b_rows % flce::TILE) || k_elems < 32 || (k_elems % 32) ||
       workgroups <= 0 || tiles_per_workgroup <= 0)
     return FLCE_ERR_BAD_SHAPE;
@@ -891,6 +891,11 @@ flce_status flce_probe(int mode, const void* A, const void* B, const void* BT, i
     case flce::PROBE_LOOP_KR_COLD: return launch(flce::probe_kernel<flce::PROBE_LOOP_KR_COLD>);
     case flce::PROBE_MFMA_16X16: return launch(flce::probe_mfma16_kernel<0>);
     case flce::PROBE_LOOP_PK: return launch(flce::probe_kernel<flce::PROBE_LOOP_PK>);
+    case flce::PROBE_PAIR_KR_KR: return launch(flce::probe_pair_kernel<flce::fast::KR, flce::fast::KR>);
+    case flce::PROBE_PAIR_PK_KR: return launch(flce::probe_pair_kernel<flce::fast::PK, flce::fast::KR>);
+    case flce::PROBE_PAIR_KR_KC: return launch(flce::probe_pair_kernel<flce::fast::KR, flce::fast::KC>);
+    case flce::PROBE_PAIR_KR_PK: return launch(flce::probe_pair_kernel<flce::fast::KR, flce::fast::PK>);
+    case flce::PROBE_PAIR_PK_PK: return launch(flce::probe_pair_kernel<flce::fast::PK, flce::fast::PK>);
   }
   return FLCE_ERR_BAD_ARG;
 }

@@ -29,6 +29,10 @@
 //   PROBE_MFMA_16X16 : PROBE_MFMA with the 16x16x32 bf16 MFMA instead (8 x 8 blocks of 4 accumulators per wavefront:
 //                    the same 128 x 128 sub-tile, the same flops per fragment, a quarter of the accumulator
 //                    registers read and written per instruction).
+//   PROBE_PAIR_*   : the complete main loop for other pairs of operand layouts (A / B): KR / KR is the dW
+//                    contraction, KR / KC the dH contraction; PK in a pair shows what a pre-tiled copy of that
+//                    operand would give.  Timing only: an operand's bytes are taken from A, B or BT as that layout,
+//                    whatever they hold.
 #pragma once
 #include "mainloop_fast.h"
 
@@ -36,7 +40,8 @@ namespace flce {
 
 enum : int {
   PROBE_MFMA = 0, PROBE_LOOP_KR = 1, PROBE_LOOP_KC = 2, PROBE_DATA_KR = 3, PROBE_DATA_KC = 4, PROBE_FREE_RUN = 5,
-  PROBE_LOOP_KR_SOFTMAX = 6, PROBE_HALF_KR = 7, PROBE_HALF_KR_SOFTMAX = 8, PROBE_LOOP_KR_COLD = 9, PROBE_MFMA_16X16 = 10, PROBE_LOOP_PK = 11
+  PROBE_LOOP_KR_SOFTMAX = 6, PROBE_HALF_KR = 7, PROBE_HALF_KR_SOFTMAX = 8, PROBE_LOOP_KR_COLD = 9, PROBE_MFMA_16X16 = 10, PROBE_LOOP_PK = 11,
+  PROBE_PAIR_KR_KR = 12, PROBE_PAIR_PK_KR = 13, PROBE_PAIR_KR_KC = 14, PROBE_PAIR_KR_PK = 15, PROBE_PAIR_PK_PK = 16
 };
 
 struct ProbeArgs {
@@ -116,6 +121,44 @@ __global__ __launch_bounds__(fast::THREADS) void probe_mfma16_kernel(ProbeArgs p
       asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][0]));
       keep += v;
     }
+  p.sink[(int64_t)blockIdx.x * fast::THREADS + threadIdx.x] = keep;
+}
+
+// One operand of a layout pair, tile index `tile`, taken from the probe's buffers (timing only).
+template <int LAYOUT>
+__device__ __forceinline__ fast::Operand probe_operand(const ProbeArgs& p, int tile, bool is_a) {
+  const bf16_t* M = is_a ? p.A : p.B;                 // [rows][k_elems]
+  const int rows = is_a ? p.a_rows : p.b_rows;
+  const int64_t ld = (int64_t)p.k_elems * 2;
+  const int row0 = (tile * TILE) % rows;
+  if (LAYOUT == fast::KC) return fast::Operand{reinterpret_cast<const char*>(M), ld, row0, rows, 0};
+  if (LAYOUT == fast::PK) return fast::Operand{reinterpret_cast<const char*>(M) + (int64_t)row0 * ld, 0, 0, 0, 0};
+  // KR: K over the rows of BT [k_elems][b_rows], a window of 256 columns
+  const int col0 = (tile * TILE) % p.b_rows;
+  return fast::Operand{reinterpret_cast<const char*>(p.BT) + (int64_t)col0 * 2, (int64_t)p.b_rows * 2, 0, p.k_elems,
+                       TILE * 2};
+}
+
+template <int LA, int LB>
+__global__ __launch_bounds__(fast::THREADS) void probe_pair_kernel(ProbeArgs p) {
+  extern __shared__ __align__(16) char lds[];
+  f32x16 acc[fast::WM][fast::WN];
+  const int n_bt = p.b_rows / TILE;
+  float keep = 0.f;
+  fast::Pipe<LA, LB> pipe;
+  for (int t = 0; t < p.tiles_per_wg; ++t) {
+    pipe.start(probe_operand<LA>(p, blockIdx.x / n_bt + t, true), probe_operand<LB>(p, blockIdx.x % n_bt, false),
+               p.k_elems, lds);
+    pipe.run(lds, acc);
+#pragma unroll
+    for (int i = 0; i < fast::WM; ++i)
+#pragma unroll
+      for (int j = 0; j < fast::WN; ++j) {
+        float v;
+        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(acc[i][j][(i * 4 + j) & 15]));
+        keep += v;
+      }
+  }
   p.sink[(int64_t)blockIdx.x * fast::THREADS + threadIdx.x] = keep;
 }
 
