@@ -172,7 +172,7 @@ flce_status flce_backward(const void* H, const void* W, const int64_t* targets, 
  *              The scratch is 12 * windows * ceil(N/256)*256 + 4 * ceil(V/1024) * d + 4 * N bytes + ~2 KiB
  *              (windows = max(4, ceil(256 / ceil(N/256))) unless FLCE_WINDOWS says otherwise): N up to about
  *              250 000 rows at d = 4096, V = 128256.  H is read in place (flce_forward's pre-tiled copy of
- *              H is what does not fit a fixed array), which costs a few per cent of speed at large d.
+ *              H is what does not fit a fixed array), which costs up to a tenth of the forward's speed.
  *   status_out, n_valid_out : device, one int32 / one int64, either may be NULL: the range flag (0 or
  *              FLCE_ERR_TARGET_RANGE) and the number of counted rows of THIS call, written on the stream
  *              (flce_last_device_status cannot be pointed at the internal array).
