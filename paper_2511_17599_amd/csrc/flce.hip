@@ -173,7 +173,8 @@ bool make_plan(int64_t N, int64_t d, int64_t V, flce_dtype dt, Plan& p, bool all
   p.hkr = allow_h_copy && p.fast;
   p.fwd_bytes = fwd_fixed + (p.hkr ? align_up(packed_block_offset(p.n_rb, (int)d), ALIGN) : 0);
   o = ALIGN;
-  p.off_Hc = o;     o = align_up(o + d * p.npad * p.esize, ALIGN);
+  // the counted rows of H: as they are (generic loop), or pre-tiled for the dW contraction (tuned loop)
+  p.off_Hc = o;     o = align_up(o + (p.fast ? packed_cols_offset((int)ceil_div(d, TILE), (int)p.npad) : d * p.npad * p.esize), ALIGN);
   p.off_rowmap = o; o = align_up(o + p.npad * 4, ALIGN);
   p.off_tgt = o;    o = align_up(o + p.npad * 4, ALIGN);
   p.off_lsec = o;   o = align_up(o + p.npad * 4, ALIGN);
@@ -378,6 +379,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
                        int64_t ignore_index, int mean, float grad_loss, void* dH, void* dW, char* ws,
                        hipStream_t st, Slice slice, PerRow rows = PerRow{nullptr, nullptr, 0.f}) {
   if (prepare_kernels<T, L>() != hipSuccess) return FLCE_ERR_HIP;
+  if (L::TRANSPOSING && !p.hkr) return FLCE_ERR_UNSUPPORTED;   // (no caller plans a backward without the copies of H)
   const int N = (int)p.N, d = (int)p.d, V = (int)p.V;
   Header* hdr = reinterpret_cast<Header*>(ws);
   T* Hc = reinterpret_cast<T*>(ws + p.off_Hc);
@@ -399,21 +401,18 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     ProfScope ps(FLCE_PROF_BWD_PREP, st);
     compact_targets_kernel<<<1, 1024, 0, st>>>(y, N, V, slice.V_total, slice.v_begin, ignore_index, npad, rowmap,
                                                tgt_c, hdr);
-    // Hc, lse and Gamma per compact row, zero rows of dH; and a second copy of Hc: transposed [d][npad] with the
-    // generic loop (the dW contraction's K-contiguous operand), pre-tiled with the tuned loop (the recompute's)
+    // lse and Gamma per compact row, zero rows of dH, and the counted rows of H packed together, twice: with the
+    // generic loop as they are (Hc) and transposed [d][npad] (the dW contraction's K-contiguous operand); with the
+    // tuned loop pre-tiled for the recompute (in HT's place) and pre-tiled the other way round for dW (in Hc's place)
     if constexpr (L::TRANSPOSING)
-      prep_rows_packed_kernel<<<dim3((unsigned)(p.npad / 64), (unsigned)ceil_div(d, 128)), 256, 0, st>>>(
-          static_cast<const char*>(H), d, rowmap, reinterpret_cast<char*>(Hc),
-          p.hkr ? reinterpret_cast<char*>(HT) : nullptr, lse, lse_c, rows.grad_rows, gam_c, y, N, slice.V_total,
-          ignore_index, static_cast<char*>(dH));
+      prep_rows_tiled_kernel<<<dim3((unsigned)(p.npad / 32), (unsigned)n_mt), 256, 0, st>>>(
+          static_cast<const char*>(H), d, rowmap, npad, reinterpret_cast<char*>(HT), reinterpret_cast<char*>(Hc), lse,
+          lse_c, rows.grad_rows, gam_c, y, N, slice.V_total, ignore_index, static_cast<char*>(dH));
     else
       prep_rows_kernel<U><<<dim3((unsigned)(p.npad / 64), (unsigned)ceil_div(d, 64)), 256, 0, st>>>(
           static_cast<const U*>(H), d, rowmap, reinterpret_cast<U*>(Hc), reinterpret_cast<U*>(HT), p.npad, lse, lse_c,
           rows.grad_rows, gam_c, y, N, slice.V_total, ignore_index, static_cast<U*>(dH));
   }
-
-  bool hkr = false;
-  if constexpr (L::TRANSPOSING) hkr = p.hkr;
 
   float* partial = reinterpret_cast<float*>(ws + p.off_partial);
   // K elements per split-K slice: whole 256-element tiles
@@ -443,7 +442,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     if (nc > 0) flags |= READ_ACC;
     flags |= (nc + 1 < p.n_nch) ? WRITE_ACC : WRITE_OUT;
     if constexpr (L::TRANSPOSING)
-      return ContractArgs<T>{Hc + (int64_t)nt0 * TILE * d, d, npad - nt0 * TILE, d, Gb, p.ld_v, n_nt * TILE,
+      return ContractArgs<T>{Hc, npad, 0, d, Gb, p.ld_v, n_nt * TILE,
                              n_nt * TILE, nt0 * TILE, n_mt, n_vt, dWacc, vt0 * TILE, static_cast<T*>(dW), vt0 * TILE,
                              V, flags, hdr, rowmap, grad_loss, mean, p.split_dw,
                              slice_len(n_nt * TILE, p.split_dw), partial, vc_pad * d};
@@ -519,11 +518,9 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
         ProfScope ps(FLCE_PROF_RECOMPUTE, st);
         // at most one workgroup per CU: each walks its share of the chunk's tiles
         const int grid = L::TRANSPOSING ? std::min(rc.n_nt * rc.n_vt, NUM_CU) : rc.n_nt * rc.n_vt;
-        if (hkr) {
-          if constexpr (L::TRANSPOSING) {
-            if (rows.grad_rows) recompute_kernel<T, L, true, true><<<grid, L::THREADS, L::LDS, st>>>(rc);
-            else recompute_kernel<T, L, true><<<grid, L::THREADS, L::LDS, st>>>(rc);
-          }
+        if constexpr (L::TRANSPOSING) {     // the tuned loop's backward always has the pre-tiled copies
+          if (rows.grad_rows) recompute_kernel<T, L, true, true><<<grid, L::THREADS, L::LDS, st>>>(rc);
+          else recompute_kernel<T, L, true><<<grid, L::THREADS, L::LDS, st>>>(rc);
         } else {
           if (rows.grad_rows) recompute_kernel<T, L, false, true><<<grid, L::THREADS, L::LDS, st>>>(rc);
           else recompute_kernel<T, L, false><<<grid, L::THREADS, L::LDS, st>>>(rc);

@@ -40,6 +40,11 @@ namespace flce {
 __host__ __device__ __forceinline__ int64_t packed_block_offset(int rb, int d) {
   return (int64_t)rb * ((int64_t)d * (TILE * 2) + FLCE_PACK_SKEW);
 }
+// The same for the transposed pre-tiled copy of a matrix with `rows` rows (a multiple of 256): byte offset of the
+// block of column tile q (256 columns), which holds rows / 32 images.
+__host__ __device__ __forceinline__ int64_t packed_cols_offset(int q, int rows) {
+  return (int64_t)q * ((int64_t)rows * (TILE * 2) + FLCE_PACK_SKEW);
+}
 
 // Main-loop policies.  A kernel is written once against this interface:
 //   THREADS, WM x WN (32x32 accumulator blocks per wavefront), LDS (dynamic LDS bytes),
@@ -635,46 +640,63 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(const char* __restrict__
   pack_rows_store(chunk, P, row / TILE, kt, d, row % TILE);
 }
 
-// The backward's row preparation for the tuned loop, one launch (same grid and thread mapping as pack_rows_kernel,
-// over the padded compact rows): Hc[c][:] = H[rowmap[c]][:] (zero behind the last counted row), HcP = its pre-tiled
-// copy (when the main loop reads one), lse_c / gam_c gathered likewise, dH rows of tokens that do not count set to
-// exactly +0.
-__global__ __launch_bounds__(256) void prep_rows_packed_kernel(const char* __restrict__ H, int d,
-                                                               const int* __restrict__ rowmap, char* __restrict__ Hc,
-                                                               char* __restrict__ HcP, const float* __restrict__ lse,
-                                                               float* __restrict__ lse_c,
-                                                               const float* __restrict__ grad_rows,
-                                                               float* __restrict__ gam_c,
-                                                               const int64_t* __restrict__ y, int N, int64_t V_total,
-                                                               int64_t ignore_index, char* __restrict__ dH) {
-  const int c = blockIdx.x * 64 + (threadIdx.x >> 2);     // compact row c, and also token c of the original order
-  const int kt = blockIdx.y * 4 + (threadIdx.x & 3);
-  const int KT = d / fast::BK;
+// The backward's row preparation for the tuned loop, one launch; block (kt, q) handles the 32 compact rows of K step
+// kt of the dW contraction and the 256 hidden columns of tile q (grid: rows_pad / 32 x ceil(d / 256), 256 threads):
+//   HcP  = the counted rows of H, packed together (zero behind the last one), pre-tiled as pack_rows_kernel does: the
+//          recompute's second operand (nullptr: not wanted);
+//   HcTP = the same rows pre-tiled the other way round, for the dW contraction, whose K index runs over the rows: per
+//          hidden tile q and K step kt the 16 KiB LDS image [256 hidden positions][32 rows] (chunk swizzle included),
+//          the images of one q following each other, block q at packed_cols_offset(q, rows_pad); hidden positions
+//          past d are zeros;
+//   lse_c / gam_c gathered likewise; dH rows of tokens that do not count set to exactly +0.
+__global__ __launch_bounds__(256) void prep_rows_tiled_kernel(const char* __restrict__ H, int d,
+                                                              const int* __restrict__ rowmap, int rows_pad,
+                                                              char* __restrict__ HcP, char* __restrict__ HcTP,
+                                                              const float* __restrict__ lse, float* __restrict__ lse_c,
+                                                              const float* __restrict__ grad_rows,
+                                                              float* __restrict__ gam_c,
+                                                              const int64_t* __restrict__ y, int N, int64_t V_total,
+                                                              int64_t ignore_index, char* __restrict__ dH) {
+  __shared__ __align__(16) uint16_t tile[32][TILE + 8];     // 528-byte rows: a column read touches every bank once
+  const int kt = blockIdx.x, q = blockIdx.y;
+  const int rr = threadIdx.x >> 3, g = threadIdx.x & 7;    // row of the K step, group of 32 hidden positions
+  const int c = kt * 32 + rr;                               // compact row c, and also token c of the original order
+  const int col0 = q * TILE + g * 32;
   const int n = rowmap[c];
-  if (blockIdx.y == 0 && (threadIdx.x & 3) == 0) {
+  if (q == 0 && g == 0) {
     lse_c[c] = (n >= 0) ? lse[n] : 0.f;
     if (grad_rows) gam_c[c] = (n >= 0) ? grad_rows[n] : 0.f;
   }
-  if (kt >= KT) return;
-  bool oor;
-  const bool dead = c < N && !target_counts(y[c], ignore_index, V_total, oor);
-  const int64_t col_bytes = (int64_t)kt * fast::BK * 2;
   u32x4 chunk[4];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) chunk[q] = u32x4{0u, 0u, 0u, 0u};
-  if (n >= 0) {
-    const u32x4* src = reinterpret_cast<const u32x4*>(H + (int64_t)n * d * 2 + col_bytes);
+  for (int i = 0; i < 4; ++i) chunk[i] = u32x4{0u, 0u, 0u, 0u};
+  if (col0 < d) {                                           // d is a multiple of 32: a group is inside or outside
+    if (n >= 0) {
+      const u32x4* src = reinterpret_cast<const u32x4*>(H + ((int64_t)n * d + col0) * 2);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) chunk[q] = src[q];
+      for (int i = 0; i < 4; ++i) chunk[i] = src[i];
+    }
+    if (HcP) pack_rows_store(chunk, HcP, c / TILE, col0 / fast::BK, d, c % TILE);
+    bool oor;
+    if (c < N && !target_counts(y[c], ignore_index, V_total, oor)) {
+      u32x4* z = reinterpret_cast<u32x4*>(dH + ((int64_t)c * d + col0) * 2);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) z[i] = u32x4{0u, 0u, 0u, 0u};
+    }
   }
-  u32x4* plain = reinterpret_cast<u32x4*>(Hc + (int64_t)c * d * 2 + col_bytes);
 #pragma unroll
-  for (int q = 0; q < 4; ++q) plain[q] = chunk[q];
-  if (HcP) pack_rows_store(chunk, HcP, c / TILE, kt, d, c % TILE);
-  if (dead) {
-    u32x4* z = reinterpret_cast<u32x4*>(dH + (int64_t)c * d * 2 + col_bytes);
+  for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&tile[rr][g * 32 + i * 8]) = chunk[i];
+  __syncthreads();
+  // thread m: the 32 rows' values at hidden position q * 256 + m, as the 64 bytes of row m of the image
+  const int m = threadIdx.x, sw = (m >> 2) & 3;
+  u32x4* dst = reinterpret_cast<u32x4*>(HcTP + packed_cols_offset(q, rows_pad) + (int64_t)kt * fast::OPER + m * 64);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) z[q] = u32x4{0u, 0u, 0u, 0u};
+  for (int ch = 0; ch < 4; ++ch) {
+    u32x4 v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      v[e] = (uint32_t)tile[ch * 8 + 2 * e][m] | ((uint32_t)tile[ch * 8 + 2 * e + 1][m] << 16);
+    dst[ch ^ sw] = v;
   }
 }
 
@@ -943,7 +965,8 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
 // OPS selects how the operands lie in memory:
 //   OPS_KC    : A[m][k], B[n][k] both K-contiguous (the transposed copies W^T, Hc^T, GT)
 //   OPS_DH_TR : A = W rows of the vocabulary chunk [k][m] (K over memory rows), B = G [n][k]
-//   OPS_DW_TR : A = Hc rows of the row chunk [k][m], B = G rows of the row chunk [k][n]
+//   OPS_DW_TR : A = the transposed pre-tiled copy of Hc (prep_rows_tiled_kernel; lda = its padded row count, the
+//               K steps of the row chunk start at image k_start / 32), B = G rows of the row chunk [k][n]
 enum : int { READ_ACC = 1, WRITE_ACC = 2, WRITE_OUT = 4, ROWS_COMPACT = 8, K_COMPACT = 16 };
 enum : int { OPS_KC = 0, OPS_DH_TR = 1, OPS_DW_TR = 2 };
 
@@ -1053,16 +1076,19 @@ __global__ __launch_bounds__(L::THREADS) void contract_kernel(ContractArgs<T> a)
     load_rows(p, orow);
     flush(acc, z, p, q, orow);
   } else {
-    fast::Pipe<fast::KR, OPS == OPS_DH_TR ? fast::KC : fast::KR> pipe;
+    fast::Pipe<OPS == OPS_DH_TR ? fast::KR : fast::PK, OPS == OPS_DH_TR ? fast::KC : fast::KR> pipe;
     auto start = [&](int p, int q, int k0, int k_elems) {
-      // A: K rows start at A (a_krows valid from there), window of 256 hidden columns at q
-      const int width = max(0, min(TILE, d - q * TILE)) * 2;
-      const fast::Operand As{reinterpret_cast<const char*>(A + (int64_t)k0 * lda) + (int64_t)q * TILE * 2, lda * 2, 0,
-                             a.a_krows - k0, width};
       if constexpr (OPS == OPS_DH_TR) {
+        // A: K rows start at A (a_krows valid from there), window of 256 hidden columns at q
+        const int width = max(0, min(TILE, d - q * TILE)) * 2;
+        const fast::Operand As{reinterpret_cast<const char*>(A + (int64_t)k0 * lda) + (int64_t)q * TILE * 2, lda * 2, 0,
+                               a.a_krows - k0, width};
         const fast::Operand Bs{reinterpret_cast<const char*>(B + k0), ldb * 2, p * TILE, a.b_rows, 0};
         pipe.start(As, Bs, k_elems, lds);
       } else {
+        // A: the images of hidden tile q, from K step (k_start + k0) / 32 on
+        const fast::Operand As{reinterpret_cast<const char*>(A) + packed_cols_offset(q, (int)lda) +
+                                   (int64_t)((a.k_start + k0) / fast::BK) * fast::OPER, 0, 0, 0, 0};
         const fast::Operand Bs{reinterpret_cast<const char*>(B + (int64_t)k0 * ldb) + (int64_t)p * TILE * 2, ldb * 2,
                                0, a.b_rows - k0, TILE * 2};
         pipe.start(As, Bs, k_elems, lds);
