@@ -106,7 +106,8 @@ const char* flce_status_string(flce_status s);
  * shape or dtype.  Host call, touches no device.
  *   forward : 12 * windows * Npad + 4 * ceil(V/1024) * d + 4 * N + O(N/256) bytes, plus Npad * d elements (and 17 KiB
  *             per 256 rows) for the pre-tiled copy of H that the tuned bf16 loop reads.  Npad = N rounded up to 256.
- *   backward: 2 * Npad * d elements (packed counted rows of H, and a transposed or pre-tiled copy of them) + 16 * Npad bytes
+ *   backward: 2 * Npad * d elements (the counted rows of H packed together, in two copies: pre-tiled for the two
+ *             kernels that read them, or plain and transposed with the generic loop; d rounded up to 256 in one) + 16 * Npad bytes
  *             + the staging tile for G: Nc x (Vc + 64) elements with Nc = min(Npad, 32768) and
  *               Vc = min(Vpad, 256 * vc) where vc = 128 tiles, or up to 512 when Nc < 8192 rows (so that
  *               Nc * Vc stays within 2^25 elements there): at most 2 GiB + 4 MiB in bf16 whatever N and V,
