@@ -414,6 +414,10 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
           rows.grad_rows, gam_c, y, N, slice.V_total, ignore_index, static_cast<U*>(dH));
   }
 
+  // With the tuned loop G is staged in blocks of 16 rows x 32 positions (1 KiB), the blocks of a row group one after
+  // the other plus one block of skew, so that row groups do not lie a power of two apart; this fits the row-major
+  // size the plan reserves (16 rows of ld_v = vc_pad + 64 elements are one block more per group).
+  const int64_t g_group_bytes = (vc_pad / 32 + 1) * 1024;
   float* partial = reinterpret_cast<float*>(ws + p.off_partial);
   // K elements per split-K slice: whole 256-element tiles
   auto slice_len = [](int k_elems, int n_split) { return (int)ceil_div(ceil_div(k_elems, TILE), n_split) * TILE; };
@@ -431,7 +435,8 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     chunk_vt(vc, vt0, n_vt);
     chunk_nt(nc, nt0, n_nt);
     return RecomputeArgs<T>{Hc, HT, static_cast<const T*>(W), tgt_c, lse_c, hdr, npad, d, V, nt0, n_nt, vt0, n_vt,
-                            Gb, p.ld_v, GT, p.ld_n, gam_c, 1.f - rows.eps, rows.eps / (float)slice.V_total};
+                            Gb, L::TRANSPOSING ? g_group_bytes : p.ld_v, GT, p.ld_n, gam_c, 1.f - rows.eps,
+                            rows.eps / (float)slice.V_total};
   };
   // dW[vocab chunk] += G^T . Hc[row chunk]   (contraction over the compact rows of the chunk)
   auto dw_args = [&](int vc, int nc, const T* Gb) {
@@ -442,7 +447,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     if (nc > 0) flags |= READ_ACC;
     flags |= (nc + 1 < p.n_nch) ? WRITE_ACC : WRITE_OUT;
     if constexpr (L::TRANSPOSING)
-      return ContractArgs<T>{Hc, npad, 0, d, Gb, p.ld_v, n_nt * TILE,
+      return ContractArgs<T>{Hc, npad, 0, d, Gb, g_group_bytes, n_nt * TILE,
                              n_nt * TILE, nt0 * TILE, n_mt, n_vt, dWacc, vt0 * TILE, static_cast<T*>(dW), vt0 * TILE,
                              V, flags, hdr, rowmap, grad_loss, mean, p.split_dw,
                              slice_len(n_nt * TILE, p.split_dw), partial, vc_pad * d};
@@ -461,7 +466,7 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     if (vc > 0) flags |= READ_ACC;
     flags |= (vc + 1 < p.n_vch) ? WRITE_ACC : WRITE_OUT;
     if constexpr (L::TRANSPOSING)
-      return ContractArgs<T>{static_cast<const T*>(W) + (int64_t)vt0 * TILE * d, d, V - vt0 * TILE, d, Gb, p.ld_v,
+      return ContractArgs<T>{static_cast<const T*>(W) + (int64_t)vt0 * TILE * d, d, V - vt0 * TILE, d, Gb, g_group_bytes,
                              n_nt * TILE, n_vt * TILE, 0, n_mt, n_nt, dHacc, 0, static_cast<T*>(dH), nt0 * TILE, npad,
                              flags, hdr, rowmap, grad_loss, mean, p.split_dh, slice_len(n_vt * TILE, p.split_dh),
                              partial - (int64_t)nt0 * TILE * d, nc_pad * d};
@@ -492,9 +497,11 @@ flce_status backward_t(const Plan& p, const void* H, const void* W, const int64_
     const int64_t first = (int64_t)body.n_nt * TILE;     // the tail's first output row, relative to the launch's
     tail.n_nt = ts.rows;
     tail.out_row0 = a.out_row0 + (int)first;
-    // G is the B operand of both: its columns are dW's output rows, its rows are dH's
-    if (is_dw) { tail.B = a.B + first; }
-    else { tail.B = a.B + first * a.ldb; tail.b_rows = a.b_rows - (int)first; }
+    // G (blocked, ldb = bytes per group of 16 rows) is the B operand of both: its columns are dW's output rows (32
+    // per block of 1 KiB), its rows are dH's
+    const char* g = reinterpret_cast<const char*>(a.B);
+    if (is_dw) { tail.B = reinterpret_cast<const T*>(g + first / 32 * 1024); }
+    else { tail.B = reinterpret_cast<const T*>(g + first / 16 * a.ldb); tail.b_rows = a.b_rows - (int)first; }
     tail.n_split = ts.slices;
     tail.k_split = slice_len(a.k_elems, ts.slices);
     tail.partial = a.partial - first * a.d;                // indexed like accbuf: by output row from the launch's first

@@ -729,7 +729,8 @@ __global__ __launch_bounds__(256) void transpose_pad_kernel(const U* __restrict_
 // forward, then
 //   g = exp(z - lse_row) - [v == y_row]            (unscaled; Gamma comes later)
 // rounded to T and written to the staging tile
-//   G [row - chunk_n0][vocab - chunk_v0]   (ldG  elements per row)
+//   G [row - chunk_n0][vocab - chunk_v0]   (ldG  elements per row; with the tuned loop in blocks of 16 rows x 32
+//                                           positions of 1 KiB, ldG = BYTES from one group of 16 rows to the next)
 // and, for main loops that need K-contiguous operands, also transposed:
 //   GT[vocab - chunk_v0][row - chunk_n0]   (ldGT elements per row)
 // Padded vocabulary columns and the padding rows behind the last counted row are 0.
@@ -876,15 +877,20 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
           }
           __builtin_amdgcn_sched_barrier(0);   // one 32x32 block at a time in VGPRs
         }
-        // the piece is complete in LDS (a wavefront's LDS operations complete in order): write it out row by row
-        const int64_t row0 = (int64_t)p * TILE + (wave & 1) * 128 + j * 32;
-        T* __restrict__ gdst = G + row0 * ldG + q * TILE + (wave >> 1) * 128 + rchunk * 8;
+        // the piece is complete in LDS (a wavefront's LDS operations complete in order): write it out, four rows of
+        // 256 bytes per instruction.  G is stored in blocks of 16 rows x 32 positions (1 KiB; the blocks of a row
+        // group along the vocabulary, row groups ldG BYTES apart), so that both contractions fetch whole blocks:
+        // a row's 16 bytes at position chunk c lie in block c / 4 at (row % 16) * 64 + (c % 4) * 16.
+        const int row0 = p * TILE + (wave & 1) * 128 + j * 32;                  // a multiple of 32: two row groups
+        const int cchunk = q * 32 + (wave >> 1) * 16 + rchunk;                  // 8-position chunk inside the chunk's row
+        char* __restrict__ gdst = reinterpret_cast<char*>(G) + (int64_t)(row0 >> 4) * ldG + (int64_t)(cchunk >> 2) * 1024 +
+                                  rrow * 64 + (cchunk & 3) * 16;
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           const int r = k * 4 + rrow;
           u32x4 vq = *reinterpret_cast<const u32x4*>(stage + r * 256 + ((rchunk ^ (r >> 1)) * 16));
           if (rrow & 1) vq = u32x4{vq[2], vq[3], vq[0], vq[1]};      // r is odd exactly when rrow is
-          *reinterpret_cast<u32x4*>(gdst + (int64_t)r * ldG) = vq;
+          *reinterpret_cast<u32x4*>(gdst + (int64_t)(k >> 2) * ldG + (k & 3) * 256) = vq;
         }
       }
     } else {
@@ -964,9 +970,10 @@ __global__ __launch_bounds__(L::THREADS) void recompute_kernel(RecomputeArgs<T> 
 //
 // OPS selects how the operands lie in memory:
 //   OPS_KC    : A[m][k], B[n][k] both K-contiguous (the transposed copies W^T, Hc^T, GT)
-//   OPS_DH_TR : A = W rows of the vocabulary chunk [k][m] (K over memory rows), B = G [n][k]
+//   OPS_DH_TR : A = W rows of the vocabulary chunk [k][m] (K over memory rows), B = G of the chunk, stored in blocks
+//               of 16 rows x 32 positions (recompute_kernel; ldb = BYTES from one group of 16 rows to the next)
 //   OPS_DW_TR : A = the transposed pre-tiled copy of Hc (prep_rows_tiled_kernel; lda = its padded row count, the
-//               K steps of the row chunk start at image k_start / 32), B = G rows of the row chunk [k][n]
+//               K steps of the row chunk start at image k_start / 32), B = the same blocked G, K over its rows
 enum : int { READ_ACC = 1, WRITE_ACC = 2, WRITE_OUT = 4, ROWS_COMPACT = 8, K_COMPACT = 16 };
 enum : int { OPS_KC = 0, OPS_DH_TR = 1, OPS_DW_TR = 2 };
 
@@ -1076,21 +1083,24 @@ __global__ __launch_bounds__(L::THREADS) void contract_kernel(ContractArgs<T> a)
     load_rows(p, orow);
     flush(acc, z, p, q, orow);
   } else {
-    fast::Pipe<OPS == OPS_DH_TR ? fast::KR : fast::PK, OPS == OPS_DH_TR ? fast::KC : fast::KR> pipe;
+    fast::Pipe<OPS == OPS_DH_TR ? fast::KR : fast::PK, OPS == OPS_DH_TR ? fast::KB : fast::RB> pipe;
     auto start = [&](int p, int q, int k0, int k_elems) {
       if constexpr (OPS == OPS_DH_TR) {
         // A: K rows start at A (a_krows valid from there), window of 256 hidden columns at q
         const int width = max(0, min(TILE, d - q * TILE)) * 2;
         const fast::Operand As{reinterpret_cast<const char*>(A + (int64_t)k0 * lda) + (int64_t)q * TILE * 2, lda * 2, 0,
                                a.a_krows - k0, width};
-        const fast::Operand Bs{reinterpret_cast<const char*>(B + k0), ldb * 2, p * TILE, a.b_rows, 0};
+        // B: G blocked (ldb = bytes from one group of 16 rows to the next), rows p * 256 ..., K from position k0
+        const fast::Operand Bs{reinterpret_cast<const char*>(B) + (int64_t)(p * (TILE / 16)) * ldb + (int64_t)(k0 / 32) * 1024,
+                               ldb, 0, 0, 0};
         pipe.start(As, Bs, k_elems, lds);
       } else {
         // A: the images of hidden tile q, from K step (k_start + k0) / 32 on
         const fast::Operand As{reinterpret_cast<const char*>(A) + packed_cols_offset(q, (int)lda) +
                                    (int64_t)((a.k_start + k0) / fast::BK) * fast::OPER, 0, 0, 0, 0};
-        const fast::Operand Bs{reinterpret_cast<const char*>(B + (int64_t)k0 * ldb) + (int64_t)p * TILE * 2, ldb * 2,
-                               0, a.b_rows - k0, TILE * 2};
+        // B: G blocked, K over its rows from row k0, the tile's 256 vocabulary positions from p * 256
+        const fast::Operand Bs{reinterpret_cast<const char*>(B) + (int64_t)(k0 / 16) * ldb + (int64_t)(p * (TILE / 32)) * 1024,
+                               ldb, 0, 0, 0};
         pipe.start(As, Bs, k_elems, lds);
       }
     };

@@ -54,7 +54,18 @@ constexpr int OPER = TILE * BK * 2;       // 16 KiB per operand per stage (eithe
 constexpr int STAGE = 2 * OPER;
 constexpr int LDS_BYTES = NS * STAGE;     // 128 KiB with 4 stages
 
-enum : int { KC = 0, KR = 1, PK = 2 };
+enum : int { KC = 0, KR = 1, PK = 2, KB = 3, RB = 4 };
+// KB and RB read a matrix that is stored in blocks of 16 rows x 32 columns (1 KiB, row-major inside), the blocks of a
+// group of 16 rows one after the other along the columns and the row groups `ld_bytes` apart ("blocked"): both of its
+// readers then fetch whole blocks, 1 KiB of consecutive bytes per request.
+//   KB: K runs along the columns (32 columns = one block per 16 tile rows and K step); the LDS tile and the fragment
+//       reads are KC's.  Operand: base = the block of the tile's first row and first K column, ld_bytes = bytes
+//       from one row group to the next.
+//   RB: K runs over the rows (two row groups per K step), the 256 tile rows are 256 consecutive columns (8 blocks);
+//       the LDS tile holds the 16 blocks as they are, [2][8][16 rows][64 B], and the fragments come from the
+//       transposing LDS read (rows of a block lie 64 bytes apart: every bank once without a swizzle).  Operand:
+//       base = the block of the first K row and the tile's first column, ld_bytes as for KB.
+constexpr bool kc_like(int layout) { return layout == KC || layout == PK || layout == KB; }
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -96,6 +107,10 @@ __device__ __forceinline__ u32x4 make_rsrc(const Operand& s, int k_elems) {
   const char* b = s.base;
   if (LAYOUT == PK) {
     n = (uint32_t)(k_elems / BK) * OPER;
+  } else if (LAYOUT == KB) {         // 16 row groups, the last one up to the end of the K extent
+    n = (uint32_t)(15 * s.ld_bytes + (int64_t)(k_elems / BK) * 1024);
+  } else if (LAYOUT == RB) {         // k_elems / 16 row groups, 8 blocks of the last one
+    if (k_elems > 0) n = (uint32_t)((int64_t)(k_elems / 16 - 1) * s.ld_bytes + 8 * 1024);
   } else if (LAYOUT == KC) {
     int vr = min(TILE_ROWS, s.rows - s.row0);
     if (vr > 0) n = (uint32_t)((int64_t)(vr - 1) * s.ld_bytes + k_elems * 2);
@@ -149,6 +164,12 @@ struct Loader {
     for (int i = 0; i < REQS; ++i) {
       if (LAYOUT == PK) {
         v[i] = (uint32_t)(wave * 4096 + i * 1024 + lane * 16);
+      } else if (LAYOUT == KB) {     // request = row group wave * 4 + i of the tile: one block, KC's chunk order
+        const int chunk = (lane & 3) ^ ((lane >> 4) & 3);
+        v[i] = (uint32_t)((wave * 4 + i) * s.ld_bytes) + (lane >> 2) * 64 + chunk * 16;
+      } else if (LAYOUT == RB) {     // request = block (row group, column block) = ((wave * 4 + i) / 8, % 8), as it is
+        const int b = wave * 4 + i;
+        v[i] = (uint32_t)((b >> 3) * s.ld_bytes) + (b & 7) * 1024 + lane * 16;
       } else if (LAYOUT == KC) {
         const int row = wave * (16 * REQS) + i * 16 + (lane >> 2);
         const int chunk = (lane & 3) ^ ((row >> 2) & 3);
@@ -159,11 +180,12 @@ struct Loader {
         v[i] = (uint32_t)(krow * s.ld_bytes) + off;
       }
     }
-    k_step = LAYOUT == PK ? OPER : LAYOUT == KC ? BK * 2 : (uint32_t)(BK * s.ld_bytes);
+    k_step = LAYOUT == PK ? OPER : LAYOUT == KC ? BK * 2 : LAYOUT == KB ? 1024 : LAYOUT == RB ? (uint32_t)(2 * s.ld_bytes)
+                                                                                      : (uint32_t)(BK * s.ld_bytes);
   }
   // request i of K tile kt into `dst` (this wavefront's slice of the operand tile of some stage)
   __device__ __forceinline__ void issue(int i, char* dst, int kt) const {
-    if (LAYOUT != KR)
+    if (kc_like(LAYOUT))
       dma16(rs, lds_address(dst + i * 1024), v[i], (uint32_t)kt * k_step);
     else   // the K advance moves to other rows: keep it in the per-lane offset, which the range check covers
       dma16(rs, lds_address(dst + i * 1024), v[i] + (uint32_t)kt * k_step, 0);
@@ -178,7 +200,7 @@ struct FragAddr {
   int o[4];   // KC: o[ks] for the two MFMA K steps (o[2], o[3] unused); KR: o[i] for the 4 blocks
   __device__ __forceinline__ void init(int wsub) {
     const int lane = threadIdx.x & 63;
-    if (LAYOUT != KR) {
+    if (kc_like(LAYOUT)) {
       const int l32 = lane & 31, half = lane >> 5, sw = (l32 >> 2) & 3;
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) o[ks] = (wsub * 32 * BLOCKS + l32) * 64 + (((ks * 2 + half) ^ sw) << 4);
@@ -186,10 +208,12 @@ struct FragAddr {
     } else {
       const int e = (lane >> 2) & 3, q = lane & 3, mg = (lane >> 4) & 1, kh = lane >> 5;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) o[i] = (8 * kh + e) * 512 + wsub * 256 + 64 * (i ^ e) + 32 * mg + 8 * q;
+      for (int i = 0; i < 4; ++i)
+        o[i] = LAYOUT == RB ? (wsub * 4 + i) * 1024 + (8 * kh + e) * 64 + 32 * mg + 8 * q
+                            : (8 * kh + e) * 512 + wsub * 256 + 64 * (i ^ e) + 32 * mg + 8 * q;
     }
   }
-  static constexpr int READS = LAYOUT != KR ? BLOCKS : 8;   // LDS reads per MFMA K step
+  static constexpr int READS = kc_like(LAYOUT) ? BLOCKS : 8;   // LDS reads per MFMA K step
 };
 
 struct Frags {
@@ -199,11 +223,14 @@ struct Frags {
 // Read number t (0 .. READS-1) of the fragments of one operand for MFMA K step ks of a stage.
 template <int LAYOUT, int BLOCKS>
 __device__ __forceinline__ void read_frag(bf16x8 (&f)[4], const FragAddr<LAYOUT, BLOCKS>& fa, const char* tile, int ks, int t) {
-  if (LAYOUT != KR) {
+  if (kc_like(LAYOUT)) {
     f[t] = *reinterpret_cast<const bf16x8*>(tile + fa.o[ks] + t * 32 * 64);
   } else {
     const int i = t >> 1, r = t & 1;
-    const s16x4 h = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fa.o[i] + (16 * ks + 4 * r) * 512));
+    // K rows 16 ks + 4 r + (0..3, +8 for the upper lanes): KR has them 512 bytes apart; RB has the 16 rows of MFMA
+    // K step ks in row group ks of the tile (8 blocks of 1 KiB), 64 bytes apart
+    const int koff = LAYOUT == RB ? ks * 8192 + r * 256 : (16 * ks + 4 * r) * 512;
+    const s16x4 h = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + fa.o[i] + koff));
     const bf16x4 hb = __builtin_bit_cast(bf16x4, h);
     if (r == 0) { f[i][0] = hb[0]; f[i][1] = hb[1]; f[i][2] = hb[2]; f[i][3] = hb[3]; }
     else        { f[i][4] = hb[0]; f[i][5] = hb[1]; f[i][6] = hb[2]; f[i][7] = hb[3]; }
