@@ -220,9 +220,12 @@ template <typename T, typename L, bool HKR>
 __global__ __launch_bounds__(L::THREADS) void fwd_tiles_kernel(
     const T* __restrict__ H, const T* __restrict__ HT, const T* __restrict__ W, const int64_t* __restrict__ y,
     int N, int d, int V, int64_t ignore_index, int64_t V_total, int64_t v_begin, int n_rb, int n_win, int n_vt,
-    float* __restrict__ part) {
+    float* __restrict__ part, int item_begin) {
   extern __shared__ __align__(16) char lds[];
-  const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  // One workgroup per item (row block x window); a launch covers the items item_begin .. item_begin + gridDim.x - 1
+  // of the raster (the host launches at most one round of workgroups at a time: all of them start together, and the
+  // workgroups of an XCD stay close enough to each other to share the operands of their raster patch in its L2).
+  const int id = item_begin + xcd_contiguous_id(blockIdx.x, gridDim.x);
   int rb, win;
   grouped_raster(id, n_rb, n_win, FLCE_FWD_GROUP, rb, win);
   const int vt_begin = (int)((int64_t)win * n_vt / n_win);
